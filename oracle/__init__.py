@@ -1,0 +1,143 @@
+"""CPU oracle for the Attention-Gate hot path (ctypes wrapper around ag_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the benchmark's
+cpu_baseline leg.  The product package never imports this module and this module never
+imports the product package.  Inputs are fp32 numpy arrays (bf16 data widened by the
+caller); floating-point results come back in fp64.
+
+Each function cites the passage it follows in ag_oracle.c.  Every function here is pinned
+by tests/test_oracle_pins.py against brute-force dense-mask attention, closed forms,
+library routines and invariants; nothing is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def lib() -> C.CDLL:
+    global _LIB
+    if _LIB is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.ag_oracle_threads.restype = C.c_int
+        L.ag_oracle_logit_threshold.restype = C.c_double
+        L.ag_oracle_logit_threshold.argtypes = [C.c_double]
+        L.ag_oracle_compact_kv.restype = C.c_int
+        L.ag_oracle_decode_step.restype = C.c_int
+        _LIB = L
+    return _LIB
+
+
+def threads() -> int:
+    return int(lib().ag_oracle_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().ag_oracle_set_threads(C.c_int(n))
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def logit_threshold(tau: float) -> float:
+    return float(lib().ag_oracle_logit_threshold(C.c_double(tau)))
+
+
+def gate(feat, w, bias, tau: float, n_sink: int = 0):
+    """feat [B,L,d_in], w [d_in,H_f], bias [H_f] -> (logits f64 [B,L,H_f], flags u8 [B,H_f,L])."""
+    feat, w, bias = _f32(feat), _f32(w), _f32(bias)
+    B, L, d_in = feat.shape
+    H_f = w.shape[1]
+    assert w.shape[0] == d_in and bias.shape == (H_f,)
+    logits = np.empty((B, L, H_f), dtype=np.float64)
+    flags = np.empty((B, H_f, L), dtype=np.uint8)
+    lib().ag_oracle_gate(_p(feat), _p(w), _p(bias), C.c_int(B), C.c_int(L), C.c_int(d_in), C.c_int(H_f),
+                         C.c_double(tau), C.c_int(n_sink), _p(logits), _p(flags))
+    return logits, flags
+
+
+def prefill_attn(q, k, v, flags, scale: float, n_recent: int = 1) -> np.ndarray:
+    """q [B,Hq,L,D], k/v [B,Hkv,L,D], flags u8 [B,Hkv,L] -> out f64 [B,Hq,L,D]."""
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    flags = np.ascontiguousarray(flags, dtype=np.uint8)
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, L, D) and v.shape == k.shape and flags.shape == (B, Hkv, L)
+    assert Hq % Hkv == 0 and n_recent >= 1
+    out = np.empty((B, Hq, L, D), dtype=np.float64)
+    lib().ag_oracle_prefill_attn(_p(q), _p(k), _p(v), _p(flags), C.c_int(B), C.c_int(L), C.c_int(Hq),
+                                 C.c_int(Hkv), C.c_int(D), C.c_double(scale), C.c_int(n_recent), _p(out))
+    return out
+
+
+@dataclass
+class Cache:
+    """Ragged per-(batch, KV head) cache.  k/v hold rows in the storage dtype given to
+    compact_kv (any dtype); decode_step needs fp32 rows."""
+    k: np.ndarray          # [total_rows, D]
+    v: np.ndarray
+    idx: np.ndarray        # int32 [total_rows]
+    row_off: np.ndarray    # int64 [U+1]
+    len: np.ndarray        # int32 [U]
+
+    def copy(self) -> "Cache":
+        return Cache(self.k.copy(), self.v.copy(), self.idx.copy(), self.row_off.copy(), self.len.copy())
+
+
+def slab_row_off(n_units: int, capacity) -> np.ndarray:
+    cap = np.broadcast_to(np.asarray(capacity, dtype=np.int64), (n_units,))
+    ro = np.zeros(n_units + 1, dtype=np.int64)
+    np.cumsum(cap, out=ro[1:])
+    return ro
+
+
+def compact_kv(k, v, flags, row_off, pos0: int = 0, fill=0):
+    """k/v [B,Hkv,L,D] (any dtype, copied byte for byte), flags u8 [B,Hkv,L] -> (Cache, overflow)."""
+    k = np.ascontiguousarray(k)
+    v = np.ascontiguousarray(v)
+    flags = np.ascontiguousarray(flags, dtype=np.uint8)
+    B, Hkv, L, D = k.shape
+    U = B * Hkv
+    row_off = np.ascontiguousarray(row_off, dtype=np.int64)
+    assert row_off.shape == (U + 1,) and v.shape == k.shape and v.dtype == k.dtype
+    total = int(row_off[-1])
+    kc = np.full((total, D), fill, dtype=k.dtype)
+    vc = np.full((total, D), fill, dtype=k.dtype)
+    idx = np.full(total, -1, dtype=np.int32)
+    ln = np.zeros(U, dtype=np.int32)
+    over = lib().ag_oracle_compact_kv(_p(k), _p(v), _p(flags), C.c_int(U), C.c_int(L),
+                                      C.c_size_t(D * k.dtype.itemsize), C.c_int(pos0), _p(row_off),
+                                      _p(kc), _p(vc), _p(idx), _p(ln))
+    return Cache(kc, vc, idx, row_off, ln), int(over)
+
+
+def decode_step(q, k_new, v_new, new_flags, pos: int, cache: Cache, scale: float):
+    """One decode step over `cache` (fp32 rows; updated in place) -> (out f64 [B,Hq,D], dropped)."""
+    q, k_new, v_new = _f32(q), _f32(k_new), _f32(v_new)
+    B, Hq, D = q.shape
+    Hkv = k_new.shape[1]
+    assert cache.k.dtype == np.float32 and cache.v.dtype == np.float32
+    assert cache.k.flags.c_contiguous and cache.v.flags.c_contiguous
+    assert cache.len.shape == (B * Hkv,) and cache.k.shape[1] == D
+    if new_flags is not None:
+        new_flags = np.ascontiguousarray(new_flags, dtype=np.uint8).reshape(B * Hkv)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    dropped = lib().ag_oracle_decode_step(_p(q), _p(k_new), _p(v_new), _p(new_flags), C.c_int(pos),
+                                          C.c_int(B), C.c_int(Hq), C.c_int(Hkv), C.c_int(D),
+                                          C.c_double(scale), _p(cache.k), _p(cache.v), _p(cache.idx),
+                                          _p(cache.row_off), _p(cache.len), _p(out))
+    return out, int(dropped)

@@ -1,0 +1,344 @@
+"""Pins for the CPU oracle: every oracle function is checked against something other than
+itself -- hand-worked fixtures from the paper's equations, brute-force dense-mask attention
+through a library matmul, closed forms, library routines and invariants.  CPU only."""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ helpers
+def eq5_mask(flags, n_recent=1):
+    """Eq. 5 written independently of the oracle as a dense 0/1 matrix (numpy indexing)."""
+    L = len(flags)
+    j = np.arange(L)[:, None]
+    t = np.arange(L)[None, :]
+    m = np.where(j < t, 0, np.where(j - t < n_recent, 1, np.asarray(flags)[None, :]))
+    return m.astype(np.float64)
+
+
+def dense_masked_attention(q, k, v, mask, scale):
+    """Eq. 2 literally: Softmax(Q K^T * scale - INF (1 - M)) V with a large finite INF, fp64."""
+    s = (q.astype(np.float64) @ k.astype(np.float64).T) * scale - 1e30 * (1.0 - mask)
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    p /= p.sum(axis=1, keepdims=True)
+    return p @ v.astype(np.float64)
+
+
+def rnd(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape).astype(np.float32)
+
+
+def read_rows(name, conv):
+    rows = []
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            rows.append([conv(x) for x in line.split()])
+    return rows
+
+
+# ------------------------------------------------------------------ fixtures from the equations
+def test_eq5_mask_fixture_matches_oracle_visibility():
+    """The hand-written Eq. 5 mask equals what the oracle attends to: with Q = 0 and one-hot V the
+    output row j is (visible set indicator) / |visible set|."""
+    flags = np.array([1, 0, 1, 0, 0], dtype=np.uint8)
+    M = np.array(read_rows("eq5_mask_n5.txt", int), dtype=np.float64)
+    assert np.array_equal(M, eq5_mask(flags))          # the helper agrees with the hand-written mask
+    L = 5
+    q = np.zeros((1, 1, L, L), dtype=np.float32)
+    k = rnd(1, 1, 1, L, L)
+    v = np.eye(L, dtype=np.float32).reshape(1, 1, L, L)
+    out = oracle.prefill_attn(q, k, v, flags.reshape(1, 1, L), 1.0)[0, 0]
+    assert np.array_equal(out > 0, M > 0)
+    np.testing.assert_allclose(out, M / M.sum(axis=1, keepdims=True), rtol=0, atol=1e-15)
+
+
+def test_uniform_attention_fixture():
+    want = np.array(read_rows("uniform_attention_n5.txt", lambda s: float(Fraction(s))))
+    flags = np.array([1, 0, 1, 0, 0], dtype=np.uint8).reshape(1, 1, 5)
+    q = np.zeros((1, 1, 5, 5), dtype=np.float32)
+    v = np.eye(5, dtype=np.float32).reshape(1, 1, 5, 5)
+    out = oracle.prefill_attn(q, rnd(2, 1, 1, 5, 5), v, flags, 0.37)[0, 0]
+    np.testing.assert_allclose(out, want, rtol=0, atol=1e-15)
+
+
+# ------------------------------------------------------------------ brute force
+def test_all_flag_patterns_small_L_vs_dense_mask():
+    L, D = 8, 4
+    q, k, v = rnd(3, L, D), rnd(4, L, D), rnd(5, L, D)
+    scale = 1.0 / math.sqrt(D)
+    pats = np.array(list(itertools.product([0, 1], repeat=L)), dtype=np.uint8)     # 256 patterns
+    P = len(pats)
+    out = oracle.prefill_attn(np.broadcast_to(q, (P, 1, L, D)), np.broadcast_to(k, (P, 1, L, D)),
+                              np.broadcast_to(v, (P, 1, L, D)), pats.reshape(P, 1, L), scale)
+    for p in range(P):
+        want = dense_masked_attention(q, k, v, eq5_mask(pats[p]), scale)
+        np.testing.assert_allclose(out[p, 0], want, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2), (4, 1)])
+def test_random_flags_vs_dense_mask_with_gqa(Hq, Hkv):
+    B, L, D = 2, 61, 16
+    q, k, v = rnd(6, B, Hq, L, D), rnd(7, B, Hkv, L, D), rnd(8, B, Hkv, L, D)
+    flags = (np.random.default_rng(9).random((B, Hkv, L)) < 0.4).astype(np.uint8)
+    scale = 0.3
+    out = oracle.prefill_attn(q, k, v, flags, scale)
+    # GQA: expand KV heads explicitly (query head i reads KV head i // (Hq/Hkv))
+    kk = np.repeat(k, Hq // Hkv, axis=1)
+    vv = np.repeat(v, Hq // Hkv, axis=1)
+    ff = np.repeat(flags, Hq // Hkv, axis=1)
+    for b in range(B):
+        for i in range(Hq):
+            want = dense_masked_attention(q[b, i], kk[b, i], vv[b, i], eq5_mask(ff[b, i]), scale)
+            np.testing.assert_allclose(out[b, i], want, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("n_recent", [1, 5, 10])
+def test_recent_window_vs_dense_mask(n_recent):
+    """Table 5 (6-1)/(6-2): the last n_recent keys stay visible whatever their flag."""
+    L, D = 40, 8
+    q, k, v = rnd(10, 1, 1, L, D), rnd(11, 1, 1, L, D), rnd(12, 1, 1, L, D)
+    flags = (np.random.default_rng(13).random((1, 1, L)) < 0.3).astype(np.uint8)
+    out = oracle.prefill_attn(q, k, v, flags, 0.5, n_recent=n_recent)[0, 0]
+    want = dense_masked_attention(q[0, 0], k[0, 0], v[0, 0], eq5_mask(flags[0, 0], n_recent), 0.5)
+    np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ special cases -> library routines
+def test_all_kept_is_causal_sdpa():
+    B, H, L, D = 2, 3, 50, 32
+    q, k, v = rnd(14, B, H, L, D), rnd(15, B, H, L, D), rnd(16, B, H, L, D)
+    out = oracle.prefill_attn(q, k, v, np.ones((B, H, L), np.uint8), 1.0 / math.sqrt(D))
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).double(), torch.from_numpy(k).double(), torch.from_numpy(v).double(),
+        is_causal=True).numpy()
+    np.testing.assert_allclose(out, want, rtol=1e-11, atol=1e-12)
+
+
+def test_all_evicted_outputs_own_value_exactly():
+    B, H, L, D = 1, 2, 33, 8
+    q, k, v = rnd(17, B, H, L, D), rnd(18, B, H, L, D), rnd(19, B, H, L, D)
+    out = oracle.prefill_attn(q, k, v, np.zeros((B, H, L), np.uint8), 0.7)
+    assert np.array_equal(out, v.astype(np.float64))
+
+
+def test_q_zero_reads_out_prefix_counts():
+    """Q = 0 => o_j = (v_j + sum_{t<j} f_t v_t) / (cnt_j + 1); with V = ones in column 0 of kept-or-self
+    rows the denominator is the exclusive prefix count of the flags plus one."""
+    L, D = 70, 3
+    flags = (np.random.default_rng(20).random(L) < 0.5).astype(np.uint8)
+    v = rnd(21, L, D)
+    out = oracle.prefill_attn(np.zeros((1, 1, L, D), np.float32), rnd(22, 1, 1, L, D), v.reshape(1, 1, L, D),
+                              flags.reshape(1, 1, L), 1.0)[0, 0]
+    cnt = np.concatenate([[0], np.cumsum(flags)[:-1]])
+    pref = np.concatenate([np.zeros((1, D)), np.cumsum(v.astype(np.float64) * flags[:, None], axis=0)[:-1]])
+    want = (v.astype(np.float64) + pref) / (cnt + 1)[:, None]
+    np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-13)
+
+
+def test_sharp_softmax_selects_best_visible_key_and_evicted_keys_vanish():
+    """Orthonormal keys, huge scale: row j returns the value of the visible key with the largest
+    score; evicting that key must switch the output to the runner-up."""
+    L = D = 12
+    k = np.eye(L, dtype=np.float32)
+    v = rnd(23, L, D)
+    # query j scores key 2 highest, key 5 second, itself third
+    q = np.zeros((L, D), np.float32)
+    q[:, 2], q[:, 5] = 3.5, 2.0
+    q[np.arange(L), np.arange(L)] += 1.0
+    for f2, f5 in [(1, 1), (0, 1), (0, 0)]:
+        flags = np.ones(L, np.uint8)
+        flags[2], flags[5] = f2, f5
+        out = oracle.prefill_attn(q.reshape(1, 1, L, D), k.reshape(1, 1, L, D), v.reshape(1, 1, L, D),
+                                  flags.reshape(1, 1, L), 200.0)[0, 0]
+        for j in range(L):
+            cand = [t for t in range(j + 1) if t == j or flags[t]]
+            best = max(cand, key=lambda t: float(q[j] @ k[t]))
+            np.testing.assert_allclose(out[j], v[best].astype(np.float64), rtol=0, atol=1e-12)
+
+
+def test_nan_in_evicted_rows_never_leaks():
+    B, H, L, D = 1, 2, 45, 8
+    q, k, v = rnd(24, B, H, L, D), rnd(25, B, H, L, D), rnd(26, B, H, L, D)
+    flags = (np.random.default_rng(27).random((B, H, L)) < 0.5).astype(np.uint8)
+    clean = oracle.prefill_attn(q, k, v, flags, 0.35)
+    kp, vp = k.copy(), v.copy()
+    ev = flags == 0
+    kp[ev] = np.nan
+    vp[ev] = np.nan
+    out = oracle.prefill_attn(q, kp, vp, flags, 0.35)
+    keep_rows = flags == 1        # evicted rows see their own (poisoned) k/v on the diagonal
+    assert np.array_equal(out[keep_rows], clean[keep_rows])
+    assert np.isfinite(out[keep_rows]).all()
+
+
+def test_units_are_independent_under_permutation():
+    B, H, L, D = 2, 4, 30, 8
+    q, k, v = rnd(28, B, H, L, D), rnd(29, B, H, L, D), rnd(30, B, H, L, D)
+    flags = (np.random.default_rng(31).random((B, H, L)) < 0.5).astype(np.uint8)
+    out = oracle.prefill_attn(q, k, v, flags, 0.4)
+    perm = np.array([2, 0, 3, 1])
+    outp = oracle.prefill_attn(q[:, perm], k[:, perm], v[:, perm], flags[:, perm], 0.4)
+    assert np.array_equal(outp, out[:, perm])
+    outb = oracle.prefill_attn(q[::-1], k[::-1], v[::-1], flags[::-1], 0.4)
+    assert np.array_equal(outb, out[::-1])
+
+
+# ------------------------------------------------------------------ gate
+def test_gate_logits_vs_library_matmul_and_threshold_rule():
+    B, L, d, H = 2, 37, 96, 5
+    x, w, bias = rnd(32, B, L, d), rnd(33, d, H) / 8, rnd(34, H)
+    for tau in (0.5, 0.3, 0.9):
+        logits, flags = oracle.gate(x, w, bias, tau)
+        want = x.astype(np.float64) @ w.astype(np.float64) + bias.astype(np.float64)
+        np.testing.assert_allclose(logits, want, rtol=1e-12, atol=1e-13)
+        sig = 1.0 / (1.0 + np.exp(-want))
+        far = np.abs(want - math.log(tau / (1 - tau))) > 1e-6
+        got = flags.transpose(0, 2, 1).astype(bool)      # [B,L,H]
+        assert np.array_equal(got[far], (sig > tau)[far])   # Eq. 4 in probability space
+
+
+def test_gate_threshold_is_strict_and_tau_half_means_positive_logit():
+    assert oracle.logit_threshold(0.5) == 0.0
+    assert abs(oracle.logit_threshold(0.3) - math.log(0.3 / 0.7)) < 1e-15
+    # one feature, weight 1: the logit is the feature itself (+ bias)
+    x = np.array([-1.0, -0.0, 0.0, 1e-30, 1.0], np.float32).reshape(1, 5, 1)
+    _, flags = oracle.gate(x, np.ones((1, 1), np.float32), np.zeros(1, np.float32), 0.5)
+    assert flags[0, 0].tolist() == [0, 0, 0, 1, 1]        # tie (s = 0 at tau = 0.5) evicts
+    # gamma inside the sigmoid (Sec. 3.5): Sigmoid(s + gamma) > tau
+    _, flags = oracle.gate(x, np.ones((1, 1), np.float32), np.full(1, 0.5, np.float32), 0.5)
+    assert flags[0, 0].tolist() == [0, 1, 1, 1, 1]
+    # forced sink tokens
+    _, flags = oracle.gate(x, np.ones((1, 1), np.float32), np.zeros(1, np.float32), 0.5, n_sink=2)
+    assert flags[0, 0].tolist() == [1, 1, 0, 1, 1]
+
+
+def test_gate_flag_layout_is_head_major():
+    B, L, d, H = 2, 6, 3, 4
+    x = rnd(35, B, L, d)
+    w = rnd(36, d, H)
+    logits, flags = oracle.gate(x, w, np.zeros(H, np.float32), 0.5)
+    assert flags.shape == (B, H, L)
+    assert np.array_equal(flags, (logits.astype(np.float32) > 0).transpose(0, 2, 1).astype(np.uint8))
+
+
+# ------------------------------------------------------------------ compaction
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+def test_compaction_invariants(dtype):
+    B, H, L, D = 2, 3, 257, 16
+    rng = np.random.default_rng(37)
+    k = rng.integers(0, 60000, (B, H, L, D)).astype(dtype)
+    v = rng.integers(0, 60000, (B, H, L, D)).astype(dtype)
+    flags = (rng.random((B, H, L)) < 0.45).astype(np.uint8)
+    flags[0, 1] = 0              # fully evicted unit
+    flags[1, 2] = 1              # fully kept unit
+    ro = oracle.slab_row_off(B * H, L + 3)
+    cache, over = oracle.compact_kv(k, v, flags, ro, pos0=1000, fill=7)
+    assert over == 0
+    fl = flags.reshape(B * H, L)
+    kk, vv = k.reshape(B * H, L, D), v.reshape(B * H, L, D)
+    assert np.array_equal(cache.len, fl.sum(axis=1))
+    for u in range(B * H):
+        n, r0 = cache.len[u], ro[u]
+        idx = cache.idx[r0:r0 + n] - 1000
+        assert np.array_equal(idx, np.flatnonzero(fl[u]))               # stable, each kept token once
+        assert np.array_equal(cache.k[r0:r0 + n], kk[u][idx])
+        assert np.array_equal(cache.v[r0:r0 + n], vv[u][idx])
+        assert (cache.k[r0 + n:ro[u + 1]] == 7).all() and (cache.idx[r0 + n:ro[u + 1]] == -1).all()
+
+
+def test_compaction_capacity_overflow_is_reported_and_bounded():
+    k = np.arange(2 * 10 * 2, dtype=np.float32).reshape(1, 2, 10, 2)
+    flags = np.ones((1, 2, 10), np.uint8)
+    ro = np.array([0, 4, 14], dtype=np.int64)
+    cache, over = oracle.compact_kv(k, k, flags, ro)
+    assert over == 1 and cache.len.tolist() == [4, 10]
+    assert np.array_equal(cache.k[:4], k[0, 0, :4]) and np.array_equal(cache.k[4:], k[0, 1])
+
+
+# ------------------------------------------------------------------ decode
+def dense_decode(q, K, V, scale):
+    s = (K.astype(np.float64) @ q.astype(np.float64)) * scale
+    p = np.exp(s - s.max())
+    return (p / p.sum()) @ V.astype(np.float64)
+
+
+def test_decode_step_vs_dense_and_append_rules():
+    B, Hq, Hkv, D = 2, 4, 2, 8
+    lens = np.array([5, 0, 1, 9], np.int32)
+    ro = oracle.slab_row_off(B * Hkv, lens + 2)
+    total = int(ro[-1])
+    cache = oracle.Cache(rnd(38, total, D), rnd(39, total, D), np.full(total, -1, np.int32), ro, lens.copy())
+    ref = cache.copy()
+    q, kn, vn = rnd(40, B, Hq, D), rnd(41, B, Hkv, D), rnd(42, B, Hkv, D)
+    nf = np.array([1, 0, 1, 0], np.uint8)
+    out, dropped = oracle.decode_step(q, kn, vn, nf, 77, cache, 0.5)
+    assert dropped == 0
+    for b in range(B):
+        for i in range(Hq):
+            u = b * Hkv + i // 2
+            K = np.concatenate([ref.k[ro[u]:ro[u] + lens[u]], kn.reshape(-1, D)[u:u + 1]])
+            V = np.concatenate([ref.v[ro[u]:ro[u] + lens[u]], vn.reshape(-1, D)[u:u + 1]])
+            np.testing.assert_allclose(out[b, i], dense_decode(q[b, i], K, V, 0.5), rtol=1e-12, atol=1e-13)
+    assert cache.len.tolist() == (lens + nf).tolist()
+    for u in range(4):
+        r = ro[u] + lens[u]
+        if nf[u]:
+            assert np.array_equal(cache.k[r], kn.reshape(-1, D)[u]) and cache.idx[r] == 77
+        else:
+            assert np.array_equal(cache.k[r], ref.k[r]) and cache.idx[r] == -1
+    # empty cache (fully evicted head): the output is the new token's own value, exactly
+    assert np.array_equal(out[0, 2], vn[0, 1].astype(np.float64))
+    assert np.array_equal(out[0, 3], vn[0, 1].astype(np.float64))
+    # NULL flags keep every generated token; capacity overflow drops the row and reports it
+    for step in range(3):
+        out, dropped = oracle.decode_step(q, kn, vn, None, 78 + step, cache, 0.5)
+    assert dropped > 0 and (cache.len <= lens + 2).all()
+
+
+def test_prefill_then_decode_equals_longer_prefill():
+    """Row L of a prefill over L+1 tokens == prefill over L tokens, compaction, one decode step."""
+    B, Hq, Hkv, L, D = 2, 4, 2, 29, 8
+    q, k, v = rnd(43, B, Hq, L + 1, D), rnd(44, B, Hkv, L + 1, D), rnd(45, B, Hkv, L + 1, D)
+    flags = (np.random.default_rng(46).random((B, Hkv, L + 1)) < 0.5).astype(np.uint8)
+    full = oracle.prefill_attn(q, k, v, flags, 0.3)
+    ro = oracle.slab_row_off(B * Hkv, L + 1)
+    cache, _ = oracle.compact_kv(k[:, :, :L], v[:, :, :L], flags[:, :, :L], ro)
+    out, _ = oracle.decode_step(q[:, :, L], k[:, :, L], v[:, :, L], flags[:, :, L], L, cache, 0.3)
+    np.testing.assert_allclose(out, full[:, :, L], rtol=1e-12, atol=1e-13)
+    # and the cache now equals the compaction of all L+1 tokens
+    cache2, _ = oracle.compact_kv(k, v, flags, ro)
+    assert np.array_equal(cache.len, cache2.len)
+    for u in range(B * Hkv):
+        n = cache.len[u]
+        assert np.array_equal(cache.k[ro[u]:ro[u] + n], cache2.k[ro[u]:ro[u] + n])
+        assert np.array_equal(cache.idx[ro[u]:ro[u] + n], cache2.idx[ro[u]:ro[u] + n])
+
+
+def test_decode_len_after_many_steps_counts_flags():
+    B, H, D, T = 1, 3, 4, 20
+    lens = np.array([2, 0, 7], np.int32)
+    ro = oracle.slab_row_off(3, lens + T)
+    total = int(ro[-1])
+    cache = oracle.Cache(rnd(47, total, D), rnd(48, total, D), np.zeros(total, np.int32), ro, lens.copy())
+    rng = np.random.default_rng(49)
+    tot = np.zeros(3, np.int64)
+    for s in range(T):
+        nf = (rng.random(3) < 0.5).astype(np.uint8)
+        tot += nf
+        oracle.decode_step(rnd(50 + s, B, H, D), rnd(80 + s, B, H, D), rnd(110 + s, B, H, D), nf, 100 + s, cache, 1.0)
+    assert np.array_equal(cache.len, lens + tot)
+    for u in range(3):
+        new_idx = cache.idx[ro[u] + lens[u]:ro[u] + cache.len[u]]
+        assert (np.diff(new_idx) > 0).all()
