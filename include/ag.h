@@ -1,0 +1,131 @@
+/*
+ * libag -- Attention-Gate (AG) KV-cache eviction, inference hot path, for AMD MI355X (gfx950).
+ *
+ * Four calls cover one attention layer:
+ *   ag_gate          token features -> one logit per (token, head) -> keep/evict flags   (Eq. 3, Eq. 4)
+ *   ag_compact_kv    keep only the flagged K/V rows, per (batch, KV head), in a ragged cache
+ *                    (Sec. 3.3: k, v of a token are retained iff its flag is 1)
+ *   ag_prefill_attn  causal attention under the flag mask with the diagonal kept       (Eq. 2, Eq. 5)
+ *   ag_decode_attn   one decoding step over the ragged cache, then append             (Sec. 3.1)
+ *
+ * Conventions
+ *   - Every tensor argument is caller-owned, contiguous DEVICE memory in the stated layout unless marked
+ *     "host".  The library never frees or keeps caller memory.  Its only allocation is the workspace made by
+ *     ag_create and released by ag_destroy.
+ *   - Work is enqueued on the given HIP stream (a hipStream_t passed as void*; NULL = default stream) and the
+ *     call returns without synchronising.  Calls on one stream are ordered.
+ *   - The return value reports errors that can be seen from the host (bad arguments, unsupported shapes,
+ *     workspace too small, launch failure).  A cache row that would exceed a unit's capacity is never
+ *     written; the kernel records it in a sticky device word that ag_poll_error reports.
+ *   - No C++ exception crosses this boundary.  An ag_ctx is not thread-safe; distinct contexts are.
+ *   - Flags: uint8, 1 (any non-zero) = retain, 0 = evict, stored head-major [B, Hkv, L].
+ *   - GQA: query head i reads KV head i / (Hq / Hkv); flags and caches are per KV head.
+ *   - Supported: dtype bf16 with D = 128 or 64 (MFMA path) and fp32 with D <= 256 (plain-ALU path);
+ *     H_f <= 32; Hq / Hkv in {1, 2, 4, 8}.
+ */
+#ifndef AG_H
+#define AG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ag_ctx ag_ctx; /* opaque; owns only its workspace */
+
+typedef enum {
+  AG_OK = 0,
+  AG_EINVAL = 1,       /* null pointer, non-positive size, Hq % Hkv != 0, tau outside (0,1), ...   */
+  AG_EUNSUPPORTED = 2, /* shape or dtype outside the supported envelope                             */
+  AG_ECAPACITY = 3,    /* a cache unit overflowed on the device (row dropped, nothing out of bounds) */
+  AG_EWORKSPACE = 4,   /* the context's workspace is smaller than this call needs                   */
+  AG_EHIP = 5          /* HIP runtime error, or a context without a device                          */
+} ag_status;
+
+typedef enum { AG_F32 = 0, AG_BF16 = 1 } ag_dtype;
+
+/*
+ * Ragged per-(batch, KV head) cache.  Unit u = b * Hkv + g owns rows [row_off[u], row_off[u+1]) of k, v and
+ * idx; its first len[u] rows are valid, in increasing token position.  All pointers are device memory.
+ */
+typedef struct {
+  void *k;                /* [total_rows, D] rows in `dtype`                                   */
+  void *v;                /* [total_rows, D]                                                   */
+  int32_t *idx;           /* [total_rows]   token position of each cached row                  */
+  const int64_t *row_off; /* [B*Hkv + 1]    first row of each unit (capacity = difference)     */
+  int32_t *len;           /* [B*Hkv]        valid rows per unit; updated by compact and decode */
+  int64_t total_rows;     /* host value: rows allocated in k, v, idx (= row_off[B*Hkv])        */
+  int32_t B, Hkv, D;
+  ag_dtype dtype;
+} ag_kv_cache;
+
+/*
+ * Context.  ag_create binds to HIP device `device` and allocates `workspace_bytes` of device workspace
+ * (ag_workspace_bytes gives a sufficient size).  device = -1 makes a context without a device: every call
+ * still validates its arguments, then returns AG_EHIP instead of launching (used to test error paths on a
+ * machine with no GPU).  ag_last_error returns a message for the last non-OK status of this context.
+ */
+ag_status ag_create(ag_ctx **out, int device, size_t workspace_bytes);
+void ag_destroy(ag_ctx *ctx);
+const char *ag_last_error(const ag_ctx *ctx);
+
+/* Workspace that covers ag_gate (d_in features), ag_compact_kv, ag_prefill_attn (with cache == NULL, which
+ * compacts into the workspace) and ag_decode_attn over caches of at most `cache_rows` rows in total. */
+size_t ag_workspace_bytes(int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, int d_in, int64_t cache_rows);
+
+/* Synchronise `stream`, read and clear the sticky device error word.  AG_OK or AG_ECAPACITY. */
+ag_status ag_poll_error(ag_ctx *ctx, void *hip_stream);
+
+/*
+ * Gate (Eq. 3 and Eq. 4; the constant inside the sigmoid is Sec. 3.5 "Initialization").
+ *   logit[b,t,h] = sum_c feat[b,t,c] * w_gate[c,h] + bias[h]          (fp32 accumulate)
+ *   flag [b,h,t] = Sigmoid(logit) > tau  <=>  logit > ln(tau/(1-tau))   (strict; compared in fp32)
+ *   flag [b,h,t] = 1 for t < n_sink
+ * feat [B, L, d_in] and w_gate [d_in, H_f] in `dtype`; bias fp32 [H_f].  feat is the hidden state for the
+ * linear gate of Sec. 3.4, or the concatenated MHA' head outputs (d_in = h' * d'_k, w_gate = W^{O'}) for the
+ * main architecture of Sec. 3.3.  logits_out fp32 [B, L, H_f] may be NULL; flags_out uint8 [B, H_f, L].
+ * bf16 needs d_in % 64 == 0.
+ */
+ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtype, int B, int L, int d_in,
+                  const void *w_gate, const float *bias, int H_f, float tau, int n_sink, float *logits_out,
+                  uint8_t *flags_out);
+
+/*
+ * KV-cache after prefilling (Sec. 3.3; Sec. 3.1 prefilling stage): stable stream compaction.
+ * For each unit, rows t of k, v [B, Hkv, L, D] with flags[b,g,t] != 0 are copied, in increasing t, to the
+ * unit's cache rows; idx gets pos0 + t and len the number of rows.  The result is unique, hence bit-exact.
+ * cache->row_off must be filled by the caller; rows beyond a unit's capacity are dropped (ag_poll_error).
+ */
+ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void *v, const uint8_t *flags,
+                        int L, int pos0, ag_kv_cache *cache);
+
+/*
+ * Flag-masked causal attention (Eq. 2 with the mask of Eq. 5).  For query head i (KV head g = i / (Hq/Hkv))
+ * and row j the visible keys are { t < j : flags[b,g,t] != 0 } plus j itself:
+ *   out[b,i,j,:] = sum_t softmax_t(scale * q_j . k_t) v_t   over that set (fp32 accumulate).
+ * q, out [B, Hq, L, D]; k, v [B, Hkv, L, D]; flags [B, Hkv, L].  `cache`, if not NULL, must be the result of
+ * ag_compact_kv on the same k, v, flags with no overflow (the kernel attends over the compacted rows and
+ * takes each row's own k_j, v_j from k, v); with NULL the call compacts into the workspace first.
+ * Evicted keys contribute exactly zero, so a fully evicted head returns out[j] = v[j].
+ */
+ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                          const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype,
+                          float scale, const ag_kv_cache *cache, void *out);
+
+/*
+ * One decoding step (Sec. 3.1 decoding stage; the gate is not run during decoding, Sec. 3.4).
+ * For every (b, query head i): keys = cache rows of unit (b, g) followed by k_new[b,g]; same for values;
+ * out[b,i,:] = softmax-weighted sum (the new token always attends to itself, Eq. 5 diagonal; an empty cache
+ * returns v_new).  Then, for every unit with new_flags == NULL or new_flags[b,g] != 0, (k_new, v_new, pos) is
+ * appended and len incremented.  All query heads of a group read the cache before the append.
+ * q, out [B, Hq, D]; k_new, v_new [B, Hkv, D] in cache->dtype; new_flags uint8 [B, Hkv] or NULL.
+ */
+ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                         const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache, void *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AG_H */

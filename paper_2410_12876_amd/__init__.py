@@ -1,0 +1,176 @@
+"""Python binding of libag (include/ag.h): argument marshalling only.
+
+Every step of the Attention-Gate path runs in the HIP kernels of libag.so; PyTorch is used
+for device memory and streams.  There is no CPU fallback: importing the library on a machine
+where libag.so has not been built raises, and every call returns the library's status as an
+exception.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libag.so")
+
+AG_OK, AG_EINVAL, AG_EUNSUPPORTED, AG_ECAPACITY, AG_EWORKSPACE, AG_EHIP = range(6)
+AG_F32, AG_BF16 = 0, 1
+STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWORKSPACE", "AG_EHIP"]
+
+EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
+           "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_decode_attn"]
+
+
+class AgError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("%s: %s" % (STATUS_NAMES[status] if 0 <= status < 6 else status, message))
+        self.status = status
+
+
+class ag_kv_cache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("idx", C.c_void_p), ("row_off", C.c_void_p),
+                ("len", C.c_void_p), ("total_rows", C.c_int64), ("B", C.c_int32), ("Hkv", C.c_int32),
+                ("D", C.c_int32), ("dtype", C.c_int)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libag.so (built by paper_2410_12876_amd/build.py); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libag.so is not built: run `python -m paper_2410_12876_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int, C.c_int64, C.c_float
+    lib.ag_create.restype = C.c_int
+    lib.ag_create.argtypes = [C.POINTER(vp), i32, C.c_size_t]
+    lib.ag_destroy.restype = None
+    lib.ag_destroy.argtypes = [vp]
+    lib.ag_last_error.restype = C.c_char_p
+    lib.ag_last_error.argtypes = [vp]
+    lib.ag_workspace_bytes.restype = C.c_size_t
+    lib.ag_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32, i64]
+    lib.ag_poll_error.restype = C.c_int
+    lib.ag_poll_error.argtypes = [vp, vp]
+    lib.ag_gate.restype = C.c_int
+    lib.ag_gate.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, f32, i32, vp, vp]
+    lib.ag_compact_kv.restype = C.c_int
+    lib.ag_compact_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.POINTER(ag_kv_cache)]
+    lib.ag_prefill_attn.restype = C.c_int
+    lib.ag_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32,
+                                    C.POINTER(ag_kv_cache), vp]
+    lib.ag_decode_attn.restype = C.c_int
+    lib.ag_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache), vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or raw integer) pointer of a tensor argument; None stays NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor arguments must be contiguous")
+    return t.data_ptr()
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return AG_BF16
+    if t.dtype == torch.float32:
+        return AG_F32
+    raise ValueError("unsupported tensor dtype %s" % t.dtype)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def workspace_bytes(B: int, L: int, Hq: int, Hkv: int, D: int, dtype: int, d_in: int = 0,
+                    cache_rows: int = 0) -> int:
+    return int(load().ag_workspace_bytes(B, L, Hq, Hkv, D, dtype, d_in, cache_rows))
+
+
+class Context:
+    """ag_ctx.  device = -1 gives a context that validates arguments but cannot launch."""
+
+    def __init__(self, device: int = 0, workspace: int = 0):
+        self._lib = load()
+        h = C.c_void_p()
+        st = self._lib.ag_create(C.byref(h), device, workspace)
+        if st != AG_OK:
+            raise AgError(st, "ag_create(device=%d, workspace=%d) failed" % (device, workspace))
+        self._h = h
+        self.device = device
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            self._lib.ag_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, st: int) -> None:
+        if st != AG_OK:
+            raise AgError(st, self._lib.ag_last_error(self._h).decode())
+
+    def poll_error(self, stream=None) -> None:
+        self._check(self._lib.ag_poll_error(self._h, _stream_ptr(stream)))
+
+
+class KVCache:
+    """ag_kv_cache over caller-made device tensors (k, v [rows, D]; idx i32; row_off i64; len i32)."""
+
+    def __init__(self, k, v, idx, row_off, len_, B: int, Hkv: int, D: int, dtype: Optional[int] = None,
+                 total_rows: Optional[int] = None):
+        self.k, self.v, self.idx, self.row_off, self.len = k, v, idx, row_off, len_
+        self.B, self.Hkv, self.D = B, Hkv, D
+        self.c = ag_kv_cache(_ptr(k), _ptr(v), _ptr(idx), _ptr(row_off), _ptr(len_),
+                             int(k.shape[0]) if total_rows is None else total_rows, B, Hkv, D,
+                             _dtype_code(k) if dtype is None else dtype)
+
+
+def ag_gate(ctx: Context, feat, w_gate, bias, tau: float, n_sink: int, logits_out, flags_out, stream=None) -> None:
+    """feat [B, L, d_in], w_gate [d_in, H_f], bias f32 [H_f] -> logits_out f32 [B, L, H_f] (or None),
+    flags_out u8 [B, H_f, L]."""
+    B, L, d_in = feat.shape
+    H_f = w_gate.shape[1]
+    ctx._check(ctx._lib.ag_gate(ctx._h, _stream_ptr(stream), _ptr(feat), _dtype_code(feat), B, L, d_in,
+                                _ptr(w_gate), _ptr(bias), H_f, tau, n_sink, _ptr(logits_out), _ptr(flags_out)))
+
+
+def ag_compact_kv(ctx: Context, k, v, flags, pos0: int, cache: KVCache, stream=None) -> None:
+    """k, v [B, Hkv, L, D], flags u8 [B, Hkv, L] -> cache (k, v, idx, len written)."""
+    L = k.shape[2]
+    ctx._check(ctx._lib.ag_compact_kv(ctx._h, _stream_ptr(stream), _ptr(k), _ptr(v), _ptr(flags), L, pos0,
+                                      C.byref(cache.c)))
+
+
+def ag_prefill_attn(ctx: Context, q, k, v, flags, scale: float, cache: Optional[KVCache], out, stream=None) -> None:
+    """q, out [B, Hq, L, D]; k, v [B, Hkv, L, D]; flags u8 [B, Hkv, L]; cache from ag_compact_kv or None."""
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    ctx._check(ctx._lib.ag_prefill_attn(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k), _ptr(v), _ptr(flags),
+                                        B, L, Hq, Hkv, D, _dtype_code(q), scale,
+                                        C.byref(cache.c) if cache is not None else None, _ptr(out)))
+
+
+def ag_decode_attn(ctx: Context, q, k_new, v_new, new_flags, pos: int, scale: float, cache: KVCache, out,
+                   stream=None) -> None:
+    """q, out [B, Hq, D]; k_new, v_new [B, Hkv, D]; new_flags u8 [B, Hkv] or None; cache updated in place."""
+    Hq = q.shape[1]
+    ctx._check(ctx._lib.ag_decode_attn(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                       _ptr(new_flags), pos, Hq, scale, C.byref(cache.c), _ptr(out)))

@@ -1,0 +1,271 @@
+// C ABI of libag: contexts, argument validation, workspace carving, kernel sequencing.
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <new>
+
+#include "ag_internal.h"
+
+bool ag_decode_supported(ag_dtype dt, int D, int G, int units);
+bool ag_prefill_supported(ag_dtype dt, int D, int G);
+
+ag_status ag_fail(ag_ctx *ctx, ag_status st, const char *fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return st;
+}
+
+namespace {
+
+constexpr int kMaxL = 1 << 22;
+
+#define AG_REQUIRE(cond, st, ...) \
+  do {                            \
+    if (!(cond)) return ag_fail(ctx, st, __VA_ARGS__); \
+  } while (0)
+
+#define AG_HIP(call)                                                                   \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) return ag_fail(ctx, AG_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+bool dtype_ok(int dt) { return dt == AG_F32 || dt == AG_BF16; }
+
+ag_status check_cache(ag_ctx *ctx, const ag_kv_cache *c) {
+  AG_REQUIRE(c->k && c->v && c->idx && c->row_off && c->len, AG_EINVAL, "cache: null pointer");
+  AG_REQUIRE(c->B > 0 && c->Hkv > 0 && c->D > 0, AG_EINVAL, "cache: B, Hkv, D must be positive");
+  AG_REQUIRE(c->total_rows >= 0, AG_EINVAL, "cache: total_rows is negative");
+  AG_REQUIRE(dtype_ok(c->dtype), AG_EINVAL, "cache: unknown dtype %d", (int)c->dtype);
+  AG_REQUIRE((c->D * ag_dtype_size(c->dtype)) % 16 == 0, AG_EUNSUPPORTED, "cache: row size must be a multiple of 16 bytes");
+  return AG_OK;
+}
+
+ws_cursor cursor(ag_ctx *ctx) { return ws_cursor{ctx->ws, ctx->ws_bytes, 0, true}; }
+
+ag_status need_device(ag_ctx *ctx) {
+  if (ctx->device < 0) return ag_fail(ctx, AG_EHIP, "context has no device (created with device = -1)");
+  hipError_t e = hipSetDevice(ctx->device);
+  if (e != hipSuccess) return ag_fail(ctx, AG_EHIP, "hipSetDevice(%d): %s", ctx->device, hipGetErrorString(e));
+  return AG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ag_status ag_create(ag_ctx **out, int device, size_t workspace_bytes) {
+  if (!out) return AG_EINVAL;
+  *out = nullptr;
+  ag_ctx *ctx = new (std::nothrow) ag_ctx();
+  if (!ctx) return AG_EHIP;
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->device = device;
+  ctx->num_cu = 256;
+  if (device >= 0) {
+    hipDeviceProp_t prop;
+    hipError_t e = hipSetDevice(device);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+    if (e == hipSuccess) {
+      ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+      ctx->ws_bytes = ag_align256(workspace_bytes);
+      e = hipMalloc((void **)&ctx->ws, ctx->ws_bytes + 256);
+    }
+    if (e == hipSuccess) {
+      ctx->d_err = reinterpret_cast<int32_t *>(ctx->ws + ctx->ws_bytes);
+      e = hipMemset(ctx->d_err, 0, 256);
+    }
+    if (e != hipSuccess) {
+      if (ctx->ws) (void)hipFree(ctx->ws);
+      delete ctx;
+      return AG_EHIP;
+    }
+  } else if (device == -1) {
+    ctx->ws_bytes = ag_align256(workspace_bytes);  // sizes are still checked; nothing is allocated
+  } else {
+    delete ctx;
+    return AG_EINVAL;
+  }
+  *out = ctx;
+  return AG_OK;
+}
+
+void ag_destroy(ag_ctx *ctx) {
+  if (!ctx) return;
+  if (ctx->device >= 0 && ctx->ws) {
+    (void)hipSetDevice(ctx->device);
+    (void)hipFree(ctx->ws);
+  }
+  delete ctx;
+}
+
+const char *ag_last_error(const ag_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+size_t ag_workspace_bytes(int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, int d_in, int64_t cache_rows) {
+  if (B <= 0 || L <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv) return 0;
+  const int units = B * Hkv;
+  const size_t scan = ag_ws_scan_bytes(units, L);
+  const size_t gate = d_in > 0 ? ag_ws_gate_bytes((int64_t)B * L, d_in, Hkv, dtype) : 0;
+  // prefill without a cache compacts into the workspace: K, V rows, idx, row_off, len
+  const size_t rows = (size_t)units * L;
+  const size_t prefill = scan + 2 * ag_align256(rows * D * ag_dtype_size(dtype)) + ag_align256(rows * 4) +
+                         ag_align256((size_t)(units + 1) * 8) + ag_align256((size_t)units * 4);
+  const size_t decode = cache_rows > 0 ? ag_ws_decode_bytes(units, Hq / Hkv, D, cache_rows) : 0;
+  size_t need = scan;
+  if (gate > need) need = gate;
+  if (prefill > need) need = prefill;
+  if (decode > need) need = decode;
+  return need + 4096;
+}
+
+ag_status ag_poll_error(ag_ctx *ctx, void *hip_stream) {
+  if (!ctx) return AG_EINVAL;
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  int32_t h = 0;
+  AG_HIP(hipMemcpyAsync(&h, ctx->d_err, sizeof(h), hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
+  AG_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
+  if (h) {
+    AG_HIP(hipMemsetAsync(ctx->d_err, 0, sizeof(h), (hipStream_t)hip_stream));
+    AG_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
+    return ag_fail(ctx, AG_ECAPACITY, "a cache unit overflowed its capacity; the extra rows were dropped");
+  }
+  return AG_OK;
+}
+
+ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtype, int B, int L, int d_in,
+                  const void *w_gate, const float *bias, int H_f, float tau, int n_sink, float *logits_out,
+                  uint8_t *flags_out) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(feat && w_gate && bias && flags_out, AG_EINVAL, "ag_gate: null pointer");
+  AG_REQUIRE(B > 0 && L > 0 && d_in > 0 && H_f > 0, AG_EINVAL, "ag_gate: B, L, d_in, H_f must be positive");
+  AG_REQUIRE(tau > 0.f && tau < 1.f, AG_EINVAL, "ag_gate: tau must lie in (0, 1)");
+  AG_REQUIRE(n_sink >= 0, AG_EINVAL, "ag_gate: n_sink is negative");
+  AG_REQUIRE(dtype_ok(dtype), AG_EINVAL, "ag_gate: unknown dtype %d", (int)dtype);
+  AG_REQUIRE(H_f <= 32, AG_EUNSUPPORTED, "ag_gate: H_f = %d exceeds 32", H_f);
+  AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_gate: L = %d exceeds %d", L, kMaxL);
+  AG_REQUIRE(dtype != AG_BF16 || d_in % 64 == 0, AG_EUNSUPPORTED, "ag_gate: bf16 needs d_in %% 64 == 0 (got %d)", d_in);
+  AG_REQUIRE(ag_ws_gate_bytes((int64_t)B * L, d_in, H_f, dtype) <= ctx->ws_bytes, AG_EWORKSPACE,
+             "ag_gate: workspace of %zu bytes is too small", ctx->ws_bytes);
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  const float thr = (float)log((double)tau / (1.0 - (double)tau));
+  ws_cursor ws = cursor(ctx);
+  hipError_t e = ag_launch_gate((hipStream_t)hip_stream, ctx->num_cu, feat, dtype, B, L, d_in, w_gate, bias, H_f, thr,
+                                n_sink, logits_out, flags_out, ws);
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_gate: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes, ws.off);
+  AG_HIP(e);
+  return AG_OK;
+}
+
+ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void *v, const uint8_t *flags, int L,
+                        int pos0, ag_kv_cache *cache) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(k && v && flags && cache, AG_EINVAL, "ag_compact_kv: null pointer");
+  AG_REQUIRE(L > 0, AG_EINVAL, "ag_compact_kv: L must be positive");
+  AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_compact_kv: L = %d exceeds %d", L, kMaxL);
+  ag_status st = check_cache(ctx, cache);
+  if (st != AG_OK) return st;
+  const int units = cache->B * cache->Hkv;
+  AG_REQUIRE(ag_ws_scan_bytes(units, L) <= ctx->ws_bytes, AG_EWORKSPACE,
+             "ag_compact_kv: workspace of %zu bytes is too small", ctx->ws_bytes);
+  st = need_device(ctx);
+  if (st != AG_OK) return st;
+  const int nw = ag_nwords(L);
+  ws_cursor ws = cursor(ctx);
+  uint64_t *words = ws.take<uint64_t>((size_t)units * nw);
+  int32_t *blk_off = ws.take<int32_t>((size_t)units * (nw + 1));
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_compact_kv: workspace too small (need %zu)", ws.off);
+  hipStream_t s = (hipStream_t)hip_stream;
+  AG_HIP(ag_launch_flag_scan(s, flags, units, L, words, blk_off));
+  AG_HIP(ag_launch_compact(s, k, v, words, blk_off, units, L, (int)(cache->D * ag_dtype_size(cache->dtype)), pos0,
+                           cache->k, cache->v, cache->idx, cache->row_off, cache->len, ctx->d_err));
+  return AG_OK;
+}
+
+ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                          const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, float scale,
+                          const ag_kv_cache *cache, void *out) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(q && k && v && flags && out, AG_EINVAL, "ag_prefill_attn: null pointer");
+  AG_REQUIRE(B > 0 && L > 0 && Hq > 0 && Hkv > 0 && D > 0, AG_EINVAL, "ag_prefill_attn: sizes must be positive");
+  AG_REQUIRE(Hq % Hkv == 0, AG_EINVAL, "ag_prefill_attn: Hq %% Hkv != 0");
+  AG_REQUIRE(scale > 0.f && isfinite(scale), AG_EINVAL, "ag_prefill_attn: scale must be positive and finite");
+  AG_REQUIRE(dtype_ok(dtype), AG_EINVAL, "ag_prefill_attn: unknown dtype %d", (int)dtype);
+  AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_prefill_attn: L = %d exceeds %d", L, kMaxL);
+  AG_REQUIRE(ag_prefill_supported(dtype, D, Hq / Hkv), AG_EUNSUPPORTED,
+             "ag_prefill_attn: unsupported dtype/D/group (%d, %d, %d)", (int)dtype, D, Hq / Hkv);
+  AG_REQUIRE((int64_t)B * Hq <= 65535, AG_EUNSUPPORTED, "ag_prefill_attn: B * Hq exceeds 65535");
+  if (cache) {
+    ag_status st = check_cache(ctx, cache);
+    if (st != AG_OK) return st;
+    AG_REQUIRE(cache->B == B && cache->Hkv == Hkv && cache->D == D && cache->dtype == dtype, AG_EINVAL,
+               "ag_prefill_attn: cache shape or dtype differs from the call's");
+  }
+  const int units = B * Hkv;
+  const int nw = ag_nwords(L);
+  const size_t esz = ag_dtype_size(dtype);
+  ws_cursor ws = cursor(ctx);
+  uint64_t *words = ws.take<uint64_t>((size_t)units * nw);
+  int32_t *blk_off = ws.take<int32_t>((size_t)units * (nw + 1));
+  const void *kc, *vc;
+  const int64_t *row_off;
+  char *wk = nullptr, *wv = nullptr;
+  int32_t *widx = nullptr, *wlen = nullptr;
+  int64_t *wro = nullptr;
+  if (cache) {
+    kc = cache->k; vc = cache->v; row_off = cache->row_off;
+  } else {
+    wk = ws.take<char>((size_t)units * L * D * esz);
+    wv = ws.take<char>((size_t)units * L * D * esz);
+    widx = ws.take<int32_t>((size_t)units * L);
+    wro = ws.take<int64_t>(units + 1);
+    wlen = ws.take<int32_t>(units);
+    kc = wk; vc = wv; row_off = wro;
+  }
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_prefill_attn: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes,
+             ws.off);
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  AG_HIP(ag_launch_flag_scan(s, flags, units, L, words, blk_off));
+  if (!cache) {
+    AG_HIP(ag_launch_slab_offsets(s, wro, units, L));
+    AG_HIP(ag_launch_compact(s, k, v, words, blk_off, units, L, (int)(D * esz), 0, wk, wv, widx, wro, wlen,
+                             ctx->d_err));
+  }
+  AG_HIP(ag_launch_prefill(s, ctx->num_cu, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, kc, vc, row_off,
+                           out));
+  return AG_OK;
+}
+
+ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                         const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache, void *out) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(q && k_new && v_new && cache && out, AG_EINVAL, "ag_decode_attn: null pointer");
+  ag_status st = check_cache(ctx, cache);
+  if (st != AG_OK) return st;
+  AG_REQUIRE(Hq > 0 && Hq % cache->Hkv == 0, AG_EINVAL, "ag_decode_attn: Hq must be a positive multiple of Hkv");
+  AG_REQUIRE(scale > 0.f && isfinite(scale), AG_EINVAL, "ag_decode_attn: scale must be positive and finite");
+  const int G = Hq / cache->Hkv, units = cache->B * cache->Hkv;
+  AG_REQUIRE(ag_decode_supported(cache->dtype, cache->D, G, units), AG_EUNSUPPORTED,
+             "ag_decode_attn: unsupported dtype/D/group/units (%d, %d, %d, %d)", (int)cache->dtype, cache->D, G, units);
+  AG_REQUIRE(ag_ws_decode_bytes(units, G, cache->D, cache->total_rows) <= ctx->ws_bytes, AG_EWORKSPACE,
+             "ag_decode_attn: workspace of %zu bytes is too small", ctx->ws_bytes);
+  st = need_device(ctx);
+  if (st != AG_OK) return st;
+  ws_cursor ws = cursor(ctx);
+  hipError_t e = ag_launch_decode((hipStream_t)hip_stream, ctx->num_cu, q, k_new, v_new, new_flags, pos, cache->B, Hq,
+                                  cache->Hkv, cache->D, cache->dtype, scale, cache->k, cache->v, cache->idx,
+                                  cache->row_off, cache->len, cache->total_rows, out, ctx->d_err, ws);
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_decode_attn: workspace too small (need %zu)", ws.off);
+  AG_HIP(e);
+  return AG_OK;
+}
+
+}  // extern "C"

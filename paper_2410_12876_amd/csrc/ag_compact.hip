@@ -1,0 +1,160 @@
+// Flag scan and KV stream compaction (Sec. 3.3: k, v of a token stay in the cache iff its flag is 1).
+//
+// Two kernels.  ag_flag_scan turns the byte flags of one (batch, KV head) unit into 64-bit keep masks (one
+// wave64 ballot per 64 tokens) and an exclusive prefix count per mask word.  ag_compact then gives every
+// wave one mask word: a lane's rank inside the word plus the word's prefix is the destination row, so the
+// surviving rows are written back-to-back (fully coalesced 16-byte stores) and evicted rows are never read.
+#include "ag_internal.h"
+
+namespace {
+
+constexpr int kScanThreads = 256;
+
+__global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_t *__restrict__ flags, int L, int nw,
+                                                                    uint64_t *__restrict__ words,
+                                                                    int32_t *__restrict__ blk_off) {
+  extern __shared__ int32_t cnts[];  // nw counts, then 256 partial sums
+  int32_t *part = cnts + nw;
+  const int u = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint8_t *f = flags + (size_t)u * L;
+  for (int w = wave; w < nw; w += kScanThreads / 64) {
+    const int t = w * 64 + lane;
+    const bool keep = t < L && f[t] != 0;
+    const uint64_t m = __ballot(keep);
+    if (lane == 0) {
+      words[(size_t)u * nw + w] = m;
+      cnts[w] = __popcll(m);
+    }
+  }
+  __syncthreads();
+  // exclusive scan of cnts[0..nw): each thread owns a contiguous run of `per` words
+  const int per = (nw + kScanThreads - 1) / kScanThreads;
+  const int w0 = tid * per, w1 = min(nw, w0 + per);
+  int32_t sum = 0;
+  for (int w = w0; w < w1; ++w) sum += cnts[w];
+  part[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < kScanThreads; d <<= 1) {
+    int32_t add = tid >= d ? part[tid - d] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  int32_t run = part[tid] - sum;  // exclusive prefix of this thread's run
+  int32_t *bo = blk_off + (size_t)u * (nw + 1);
+  for (int w = w0; w < w1; ++w) {
+    bo[w] = run;
+    run += cnts[w];
+  }
+  if (tid == kScanThreads - 1) bo[nw] = part[tid];
+}
+
+// LPR = lanes that share one row (16 bytes each); rows wider than 1 KiB loop over segments.
+template <int LPR>
+__global__ __launch_bounds__(256) void ag_compact_kernel(const uint4 *__restrict__ k, const uint4 *__restrict__ v,
+                                                         const uint64_t *__restrict__ words,
+                                                         const int32_t *__restrict__ blk_off, int nw, int L,
+                                                         int row_vec, int pos0, uint4 *__restrict__ kc,
+                                                         uint4 *__restrict__ vc, int32_t *__restrict__ idx,
+                                                         const int64_t *__restrict__ row_off,
+                                                         int32_t *__restrict__ len, int32_t *__restrict__ d_err) {
+  __shared__ uint8_t sel[4][64];
+  const int u = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int w = blockIdx.x * 4 + wave;
+  if (w >= nw) return;  // whole wave leaves together; no block-wide barrier below
+  const uint64_t word = words[(size_t)u * nw + w];
+  const int32_t *bo = blk_off + (size_t)u * (nw + 1);
+  const int64_t base = bo[w];
+  const int n = __popcll(word);
+  const int64_t r0 = row_off[u];
+  const int64_t cap = row_off[u + 1] - r0;
+  if (w == nw - 1 && lane == 0) {
+    const int64_t total = bo[nw];
+    len[u] = (int32_t)(total < cap ? total : cap);
+    if (total > cap) atomicOr(d_err, 1);
+  }
+  if (n == 0) return;
+  const bool keep = (word >> lane) & 1ull;
+  const int rank = __popcll(word & ((1ull << lane) - 1ull));
+  if (keep) {
+    sel[wave][rank] = (uint8_t)lane;
+    if (base + rank < cap) idx[r0 + base + rank] = pos0 + w * 64 + lane;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  constexpr int RPI = 64 / LPR;  // rows per wave iteration
+  constexpr int UN = 4;          // independent rows in flight per lane group
+  const int sub = lane / LPR, seg0 = lane % LPR;
+  const size_t src_unit = (size_t)u * L * row_vec;
+  for (int c0 = 0; c0 < n; c0 += RPI * UN) {
+    for (int seg = seg0; seg < row_vec; seg += LPR) {
+      uint4 kk[UN], vv[UN];
+      bool ok[UN];
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        const int c = c0 + j * RPI + sub;
+        ok[j] = c < n && base + c < cap;
+        if (ok[j]) {
+          const size_t src = src_unit + (size_t)(w * 64 + sel[wave][c]) * row_vec + seg;
+          kk[j] = k[src];
+          vv[j] = v[src];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        const int c = c0 + j * RPI + sub;
+        if (ok[j]) {
+          const size_t dst = (size_t)(r0 + base + c) * row_vec + seg;
+          kc[dst] = kk[j];
+          vc[dst] = vv[j];
+        }
+      }
+    }
+  }
+}
+
+__global__ void ag_slab_offsets_kernel(int64_t *row_off, int units, int L) {
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u <= units) row_off[u] = (int64_t)u * L;
+}
+
+}  // namespace
+
+hipError_t ag_launch_slab_offsets(hipStream_t s, int64_t *row_off, int units, int L) {
+  hipLaunchKernelGGL(ag_slab_offsets_kernel, dim3((units + 256) / 256), dim3(256), 0, s, row_off, units, L);
+  return hipGetLastError();
+}
+
+size_t ag_ws_scan_bytes(int units, int L) {
+  const size_t nw = ag_nwords(L);
+  return ag_align256((size_t)units * nw * sizeof(uint64_t)) + ag_align256((size_t)units * (nw + 1) * sizeof(int32_t));
+}
+
+hipError_t ag_launch_flag_scan(hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
+                               int32_t *blk_off) {
+  const int nw = ag_nwords(L);
+  const size_t shmem = (size_t)(nw + kScanThreads) * sizeof(int32_t);
+  hipLaunchKernelGGL(ag_flag_scan_kernel, dim3(units), dim3(kScanThreads), shmem, s, flags, L, nw, words, blk_off);
+  return hipGetLastError();
+}
+
+hipError_t ag_launch_compact(hipStream_t s, const void *k, const void *v, const uint64_t *words,
+                             const int32_t *blk_off, int units, int L, int row_bytes, int pos0, void *kc, void *vc,
+                             int32_t *idx, const int64_t *row_off, int32_t *len, int32_t *d_err) {
+  const int nw = ag_nwords(L);
+  const int row_vec = row_bytes / 16;
+  const dim3 grid((nw + 3) / 4, units), block(256);
+#define AG_COMPACT(LPR)                                                                                           \
+  hipLaunchKernelGGL(ag_compact_kernel<LPR>, grid, block, 0, s, (const uint4 *)k, (const uint4 *)v, words, blk_off, \
+                     nw, L, row_vec, pos0, (uint4 *)kc, (uint4 *)vc, idx, row_off, len, d_err)
+  if (row_vec <= 8) AG_COMPACT(8);
+  else if (row_vec <= 16) AG_COMPACT(16);
+  else if (row_vec <= 32) AG_COMPACT(32);
+  else AG_COMPACT(64);
+#undef AG_COMPACT
+  return hipGetLastError();
+}

@@ -1,0 +1,366 @@
+// Decode attention over ragged per-(batch, KV head) caches (Sec. 3.1, decoding stage) -- split-K.
+//
+// The step is bandwidth-bound: every cached K and V row is read once.  Work is cut into items of kChunk rows
+// of one unit; the item list is built on the device from len[] (no host read-back), and a persistent grid
+// walks it round-robin.  Inside an item each group of LPR lanes owns one row per load (16 bytes per lane, a
+// wave reads 1 KiB of contiguous rows per instruction), keeps an online-softmax state per query head of the
+// group, and the states are merged through LDS into one (max, sum, weighted-V) record per item and head.
+// A second kernel merges the records of each (batch, query head) with the new token's own key/value -- the
+// diagonal of Eq. 5 -- normalises, and appends the new row to the cache when its flag says so.
+#include "ag_internal.h"
+
+namespace {
+
+constexpr int kChunk = 256;      // rows per work item
+constexpr int kMaxUnits = 8192;  // units whose item offsets fit in LDS
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <typename T> struct elems;  // element count and widening of one 16-byte vector
+template <> struct elems<float> {
+  static constexpr int n = 4;
+  static __device__ __forceinline__ void widen(const uint4 &r, float *f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+template <> struct elems<uint16_t> {  // bf16 bit patterns
+  static constexpr int n = 8;
+  static __device__ __forceinline__ void widen(const uint4 &r, float *f) {
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+};
+
+__device__ __forceinline__ float widen1(float x) { return x; }
+__device__ __forceinline__ float widen1(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+__device__ __forceinline__ void narrow1(float x, float *o) { *o = x; }
+__device__ __forceinline__ void narrow1(float x, uint16_t *o) {  // round to nearest even
+  uint32_t u = __float_as_uint(x);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  *o = (uint16_t)(u >> 16);
+}
+
+// valid rows of a unit, never more than its slab holds
+__device__ __forceinline__ int unit_len(const int32_t *__restrict__ len, const int64_t *__restrict__ row_off, int u) {
+  const int64_t cap = row_off[u + 1] - row_off[u];
+  const int n = len[u];
+  return n < 0 ? 0 : (n < cap ? n : (int)cap);
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+// Sum over aligned groups of LPR lanes; every lane of the group gets the sum.
+template <int LPR> __device__ __forceinline__ float group_sum(float x) {
+  x += dpp<0xB1>(x);                           // quad_perm [1,0,3,2]
+  x += dpp<0x4E>(x);                           // quad_perm [2,3,0,1]
+  if (LPR >= 8) x += dpp<0x141>(x);            // row_half_mirror
+  if (LPR >= 16) x += dpp<0x140>(x);           // row_mirror
+  if (LPR >= 32) x += __shfl_xor(x, 16, 64);
+  if (LPR >= 64) x += __shfl_xor(x, 32, 64);
+  return x;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Kernel 1: per-item partial attention.
+//   item_off [U+1] (global copy for the merge kernel), pm/pl [items*G], pacc [items*G, D]
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restrict__ q, const T *__restrict__ kc,
+                                                                const T *__restrict__ vc,
+                                                                const int64_t *__restrict__ row_off,
+                                                                const int32_t *__restrict__ len, int U, int Hkv,
+                                                                float qscale, int32_t *__restrict__ item_off_g,
+                                                                float *__restrict__ pm, float *__restrict__ pl,
+                                                                float *__restrict__ pacc) {
+  constexpr int EPL = elems<T>::n;        // elements per lane
+  constexpr int LPR = D / EPL;            // lanes per row
+  constexpr int GPW = 64 / LPR;           // rows per wave load
+  constexpr int NST = 4 * GPW;            // online-softmax states per block
+  constexpr int UN = 4;                   // rows in flight per lane group
+  extern __shared__ int32_t smem[];
+  int32_t *item_off = smem;               // [U+1]
+  int32_t *scan = smem + (U + 1);         // [256]
+  float *st = reinterpret_cast<float *>(scan + 256);  // [NST][G][D+2]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  // ---- item offsets: exclusive scan of ceil(len/kChunk) over units ----
+  const int per = (U + 255) / 256;
+  const int u0 = tid * per, u1 = min(U, u0 + per);
+  int32_t sum = 0;
+  for (int u = u0; u < u1; ++u) sum += (unit_len(len, row_off, u) + kChunk - 1) / kChunk;
+  scan[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < 256; d <<= 1) {
+    int32_t add = tid >= d ? scan[tid - d] : 0;
+    __syncthreads();
+    scan[tid] += add;
+    __syncthreads();
+  }
+  int32_t run = scan[tid] - sum;
+  for (int u = u0; u < u1; ++u) {
+    item_off[u] = run;
+    run += (unit_len(len, row_off, u) + kChunk - 1) / kChunk;
+  }
+  if (tid == 255) item_off[U] = scan[255];
+  __syncthreads();
+  const int n_items = item_off[U];
+  if (blockIdx.x == 0)
+    for (int u = tid; u <= U; u += 256) item_off_g[u] = item_off[u];
+
+  const int grp = lane / LPR, seg = lane % LPR;
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    // unit of this item: last u with item_off[u] <= item
+    int lo = 0, hi = U;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (item_off[mid] <= item) lo = mid; else hi = mid;
+    }
+    const int u = lo;
+    const int c = item - item_off[u];
+    const int b = u / Hkv, g = u - b * Hkv;
+    const int n = unit_len(len, row_off, u);
+    const int row_end = min(n, (c + 1) * kChunk);
+    const int wrow0 = c * kChunk + wave * (kChunk / 4);
+    const uint4 *K = reinterpret_cast<const uint4 *>(kc + (size_t)row_off[u] * D);
+    const uint4 *V = reinterpret_cast<const uint4 *>(vc + (size_t)row_off[u] * D);
+
+    float qf[G][EPL];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) {
+      const uint4 r = reinterpret_cast<const uint4 *>(q + ((size_t)(b * Hkv + g) * G + gg) * D)[seg];
+      elems<T>::widen(r, qf[gg]);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qf[gg][e] *= qscale;
+    }
+    float m[G], l[G], acc[G][EPL];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) {
+      m[gg] = -INFINITY; l[gg] = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[gg][e] = 0.f;
+    }
+
+    for (int it0 = 0; it0 < kChunk / 4 / GPW; it0 += UN) {
+      if (wrow0 + it0 * GPW >= row_end) break;  // wave-uniform
+      uint4 kk[UN], vv[UN];
+      bool ok[UN];
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        const int r = wrow0 + (it0 + j) * GPW + grp;
+        ok[j] = r < row_end;
+        kk[j] = make_uint4(0, 0, 0, 0);
+        vv[j] = make_uint4(0, 0, 0, 0);
+        if (ok[j]) {
+          kk[j] = K[(size_t)r * LPR + seg];
+          vv[j] = V[(size_t)r * LPR + seg];
+        }
+      }
+      float s[G][UN];
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        float kf[EPL];
+        elems<T>::widen(kk[j], kf);
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) {
+          float d = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) d = fmaf(qf[gg][e], kf[e], d);
+          d = group_sum<LPR>(d);
+          s[gg][j] = ok[j] ? d : -INFINITY;
+        }
+      }
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) {
+        float mn = m[gg];
+#pragma unroll
+        for (int j = 0; j < UN; ++j) mn = fmaxf(mn, s[gg][j]);
+        if (mn == -INFINITY) continue;  // this lane group has seen no valid row yet
+        const float alpha = exp2f(m[gg] - mn);  // m = -inf -> 0
+        m[gg] = mn;
+        l[gg] *= alpha;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[gg][e] *= alpha;
+#pragma unroll
+        for (int j = 0; j < UN; ++j) s[gg][j] = exp2f(s[gg][j] - mn);  // -inf -> 0
+      }
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        float vf[EPL];
+        elems<T>::widen(vv[j], vf);
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) {
+          const float p = m[gg] == -INFINITY ? 0.f : s[gg][j];
+          l[gg] += p;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[gg][e] = fmaf(p, vf[e], acc[gg][e]);
+        }
+      }
+    }
+
+    // ---- merge the NST states of the block ----
+    const int sidx = wave * GPW + grp;
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) {
+      float *rec = st + ((size_t)sidx * G + gg) * (D + 2);
+      if (seg == 0) { rec[0] = m[gg]; rec[1] = l[gg]; }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) rec[2 + seg * EPL + e] = acc[gg][e];
+    }
+    __syncthreads();
+    for (int o = tid; o < G * D; o += 256) {
+      const int gg = o / D, d = o - gg * D;
+      float M = -INFINITY;
+#pragma unroll
+      for (int sI = 0; sI < NST; ++sI) M = fmaxf(M, st[((size_t)sI * G + gg) * (D + 2)]);
+      float L = 0.f, A = 0.f;
+#pragma unroll
+      for (int sI = 0; sI < NST; ++sI) {
+        const float *rec = st + ((size_t)sI * G + gg) * (D + 2);
+        const float w = rec[0] == -INFINITY ? 0.f : exp2f(rec[0] - M);
+        L = fmaf(w, rec[1], L);
+        A = fmaf(w, rec[2 + d], A);
+      }
+      const size_t pr = (size_t)item * G + gg;
+      pacc[pr * D + d] = A;
+      if (d == 0) { pm[pr] = M; pl[pr] = L; }
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Kernel 2: one block per (batch, query head): merge item records + the new token itself, write out, append.
+template <typename T, int D>
+__global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict__ q, const T *__restrict__ k_new,
+                                                            const T *__restrict__ v_new,
+                                                            const uint8_t *__restrict__ new_flags, int pos, int Hq,
+                                                            int Hkv, float qscale,
+                                                            const int32_t *__restrict__ item_off,
+                                                            const float *__restrict__ pm, const float *__restrict__ pl,
+                                                            const float *__restrict__ pacc, T *__restrict__ kc,
+                                                            T *__restrict__ vc, int32_t *__restrict__ idx,
+                                                            const int64_t *__restrict__ row_off,
+                                                            int32_t *__restrict__ len, T *__restrict__ out,
+                                                            int32_t *__restrict__ d_err) {
+  __shared__ float red[D / 64 > 0 ? D / 64 : 1];
+  const int G = Hq / Hkv;
+  const int bi = blockIdx.x;  // b * Hq + i
+  const int b = bi / Hq, i = bi - b * Hq;
+  const int g = i / G, gg = i - g * G;
+  const int u = b * Hkv + g;
+  const int d = threadIdx.x;
+  const float kn = widen1(k_new[(size_t)u * D + d]);
+  const float vn = widen1(v_new[(size_t)u * D + d]);
+  // self score: scale * q . k_new (in log2 units)
+  float part = widen1(q[(size_t)bi * D + d]) * qscale * kn;
+  for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+  if ((d & 63) == 0) red[d >> 6] = part;
+  __syncthreads();
+  float s_self = 0.f;
+#pragma unroll
+  for (int w = 0; w < (D + 63) / 64; ++w) s_self += red[w];
+
+  const int i0 = item_off[u], i1 = item_off[u + 1];
+  float M = s_self;
+  for (int it = i0; it < i1; ++it) M = fmaxf(M, pm[(size_t)it * G + gg]);
+  float L = exp2f(s_self - M);
+  float A = L * vn;
+  for (int it = i0; it < i1; ++it) {
+    const size_t pr = (size_t)it * G + gg;
+    const float w = exp2f(pm[pr] - M);
+    L = fmaf(w, pl[pr], L);
+    A = fmaf(w, pacc[pr * D + d], A);
+  }
+  narrow1(A / L, &out[(size_t)bi * D + d]);
+
+  if (gg == 0 && (new_flags == nullptr || new_flags[u] != 0)) {
+    const int n = len[u];
+    const int64_t r0 = row_off[u], cap = row_off[u + 1] - r0;
+    __syncthreads();  // every thread has read len[u] before it changes
+    if (n < cap) {
+      kc[(size_t)(r0 + n) * D + d] = k_new[(size_t)u * D + d];
+      vc[(size_t)(r0 + n) * D + d] = v_new[(size_t)u * D + d];
+      if (d == 0) { idx[r0 + n] = pos; len[u] = n + 1; }
+    } else if (d == 0) {
+      atomicOr(d_err, 1);
+    }
+  }
+}
+
+int64_t max_items(int units, int64_t cache_rows) { return cache_rows / kChunk + units; }
+
+template <typename T, int D, int G>
+hipError_t launch_t(hipStream_t s, int num_cu, const void *q, const void *k_new, const void *v_new,
+                    const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, float scale, void *kc, void *vc,
+                    int32_t *idx, const int64_t *row_off, int32_t *len, int64_t total_rows, void *out, int32_t *d_err,
+                    ws_cursor &ws) {
+  const int U = B * Hkv;
+  const int64_t items = max_items(U, total_rows);
+  int32_t *item_off = ws.take<int32_t>(U + 1);
+  float *pm = ws.take<float>(items * G);
+  float *pl = ws.take<float>(items * G);
+  float *pacc = ws.take<float>(items * G * D);
+  if (!ws.ok) return hipSuccess;
+  constexpr int EPL = elems<T>::n, LPR = D / EPL, GPW = 64 / LPR, NST = 4 * GPW;
+  const size_t shmem = (size_t)(U + 1 + 256) * 4 + (size_t)NST * G * (D + 2) * 4;
+  const float qscale = scale * kLog2e;
+  int blocks = num_cu * 4;
+  if (blocks > items) blocks = (int)items;
+  if (blocks < 1) blocks = 1;
+  if (shmem > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ag_decode_partial_kernel<T, D, G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((ag_decode_partial_kernel<T, D, G>), dim3(blocks), dim3(256), shmem, s, (const T *)q,
+                     (const T *)kc, (const T *)vc, row_off, len, U, Hkv, qscale, item_off, pm, pl, pacc);
+  hipLaunchKernelGGL((ag_decode_merge_kernel<T, D>), dim3(B * Hq), dim3(D), 0, s, (const T *)q, (const T *)k_new,
+                     (const T *)v_new, new_flags, pos, Hq, Hkv, qscale, item_off, pm, pl, pacc, (T *)kc, (T *)vc, idx,
+                     row_off, len, (T *)out, d_err);
+  return hipGetLastError();
+}
+
+template <typename T, int D, typename... A>
+hipError_t launch_g(int G, A &&...a) {
+  switch (G) {
+    case 1: return launch_t<T, D, 1>(a...);
+    case 2: return launch_t<T, D, 2>(a...);
+    case 4: return launch_t<T, D, 4>(a...);
+    case 8: return launch_t<T, D, 8>(a...);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+size_t ag_ws_decode_bytes(int units, int G, int D, int64_t cache_rows) {
+  const int64_t items = max_items(units, cache_rows);
+  return ag_align256((size_t)(units + 1) * 4) + 2 * ag_align256((size_t)items * G * 4) +
+         ag_align256((size_t)items * G * D * 4);
+}
+
+bool ag_decode_supported(ag_dtype dt, int D, int G, int units) {
+  if (units > kMaxUnits) return false;
+  if (!(G == 1 || G == 2 || G == 4 || G == 8)) return false;
+  return dt == AG_BF16 ? (D == 64 || D == 128) : (D == 64 || D == 128);
+}
+
+hipError_t ag_launch_decode(hipStream_t s, int num_cu, const void *q, const void *k_new, const void *v_new,
+                            const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
+                            float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
+                            int64_t total_rows, void *out, int32_t *d_err, ws_cursor &ws) {
+  const int G = Hq / Hkv;
+#define AG_DEC(T, DD)                                                                                              \
+  return launch_g<T, DD>(G, s, num_cu, q, k_new, v_new, new_flags, pos, B, Hq, Hkv, scale, kc, vc, idx, row_off, len, \
+                         total_rows, out, d_err, ws)
+  if (dt == AG_BF16) {
+    if (D == 64) AG_DEC(uint16_t, 64);
+    if (D == 128) AG_DEC(uint16_t, 128);
+  } else {
+    if (D == 64) AG_DEC(float, 64);
+    if (D == 128) AG_DEC(float, 128);
+  }
+#undef AG_DEC
+  return hipErrorInvalidValue;
+}

@@ -1,0 +1,192 @@
+// Gate (Eq. 3, Eq. 4): features [tokens, d_in] x W [d_in, H_f] -> logits -> keep flags.
+//
+// The product is a skinny GEMM (N = H_f <= 32) whose cost is reading the features once from HBM.  The bf16
+// path runs it on MFMA (v_mfma_f32_32x32x16_bf16, N padded to 32): every wave owns MT x 32 tokens and a slice
+// of the K range, streams its feature rows with 16-byte loads that together cover whole 128-byte lines, and
+// takes the matching W fragments from a pre-packed copy that stays in L2.  K is split over the 4 waves of a
+// workgroup and, when there are few tokens, over several workgroups; partial sums go to the workspace and a
+// second kernel adds them in a fixed order (so flags are reproducible run to run), adds the bias, compares
+// with the logit-space threshold and writes the flags head-major.
+#include "ag_internal.h"
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kNP = 32;  // padded head count (MFMA N)
+
+// W [d_in, H_f] bf16 -> fragment order: [(chunk*4 + step)*64 + lane][8], lane = (n = lane%32, kb = lane/32),
+// element j = W[chunk*64 + kb*32 + step*8 + j][n]  (0 for n >= H_f).
+__global__ void ag_gate_pack_w(const uint16_t *__restrict__ w, int d_in, int H_f, uint16_t *__restrict__ wp) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;  // one packed element
+  if (i >= d_in * kNP) return;
+  const int j = i & 7, lane = (i >> 3) & 63, step = (i >> 9) & 3, chunk = i >> 11;
+  const int n = lane & 31, kb = lane >> 5;
+  const int kk = chunk * 64 + kb * 32 + step * 8 + j;
+  wp[i] = n < H_f ? w[(size_t)kk * H_f + n] : (uint16_t)0;
+}
+
+// grid = (token tiles, K splits); block = 256.  partial [S][tokens_pad][32] fp32.
+template <int MT>
+__global__ __launch_bounds__(256) void ag_gate_mfma_kernel(const uint16_t *__restrict__ x, const uint4 *__restrict__ wp,
+                                                           int64_t tokens, int d_in, int chunks_per_split,
+                                                           float *__restrict__ partial, int64_t tokens_pad) {
+  __shared__ float red[4][MT][32][33];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = lane & 31, kb = lane >> 5;
+  const int64_t tok0 = (int64_t)blockIdx.x * (32 * MT);
+  const int nchunks = d_in / 64;
+  const int c_begin = blockIdx.y * chunks_per_split;
+  const int c_end = min(nchunks, c_begin + chunks_per_split);
+
+  const uint4 *rows[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    int64_t tok = tok0 + t * 32 + m;
+    if (tok >= tokens) tok = tokens - 1;  // clamp: the row is read but its result is never written
+    rows[t] = reinterpret_cast<const uint4 *>(x + (size_t)tok * d_in + kb * 32);
+  }
+  f32x16 acc[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  for (int c = c_begin + wave; c < c_end; c += 4) {
+    uint4 a[MT][4], b[4];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) a[t][s] = rows[t][c * 8 + s];  // 64 k = 8 uint4 per row; this lane's half
+#pragma unroll
+    for (int s = 0; s < 4; ++s) b[s] = wp[((size_t)c * 4 + s) * 64 + lane];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[t][s]),
+                                                         __builtin_bit_cast(bf16x8, b[s]), acc[t], 0, 0, 0);
+  }
+  // C layout of the 32x32 tile: acc[r] is (row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32)
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][t][8 * (r >> 2) + 4 * kb + (r & 3)][m] = acc[t][r];
+  __syncthreads();
+  float *dst = partial + ((size_t)blockIdx.y * tokens_pad + tok0) * kNP;
+  for (int e = threadIdx.x; e < MT * 32 * 32; e += 256) {
+    const int t = e >> 10, row = (e >> 5) & 31, col = e & 31;
+    dst[e] = red[0][t][row][col] + red[1][t][row][col] + red[2][t][row][col] + red[3][t][row][col];
+  }
+}
+
+// fp32 features: plain ALU path (one thread per (token, padded head)), partial [1][tokens_pad][32].
+__global__ __launch_bounds__(256) void ag_gate_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                          int64_t tokens, int d_in, int H_f,
+                                                          float *__restrict__ partial) {
+  const int h = threadIdx.x & 31;
+  const int64_t tok = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+  if (tok >= tokens) return;
+  float s = 0.f;
+  if (h < H_f) {
+    const float *xr = x + (size_t)tok * d_in;
+    for (int c = 0; c < d_in; ++c) s = fmaf(xr[c], w[(size_t)c * H_f + h], s);
+  }
+  partial[(size_t)tok * kNP + h] = s;
+}
+
+// Sum the K splits in order, add bias, threshold, write logits [tokens, H_f] and flags [B, H_f, L].
+__global__ __launch_bounds__(256) void ag_gate_finalize_kernel(const float *__restrict__ partial, int splits,
+                                                               int64_t tokens_pad, int64_t tokens, int L, int H_f,
+                                                               const float *__restrict__ bias, float thr, int n_sink,
+                                                               float *__restrict__ logits,
+                                                               uint8_t *__restrict__ flags) {
+  __shared__ uint8_t fl[kNP][64];
+  const int64_t tok0 = (int64_t)blockIdx.x * 64;
+  for (int e = threadIdx.x; e < 64 * H_f; e += 256) {
+    const int tl = e / H_f, h = e - tl * H_f;
+    const int64_t tok = tok0 + tl;
+    if (tok >= tokens) continue;
+    float s = 0.f;
+    for (int sp = 0; sp < splits; ++sp) s += partial[((size_t)sp * tokens_pad + tok) * kNP + h];
+    s += bias[h];
+    if (logits) logits[(size_t)tok * H_f + h] = s;
+    const int t = (int)(tok % L);
+    fl[h][tl] = (s > thr || t < n_sink) ? 1 : 0;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * H_f; e += 256) {
+    const int h = e >> 6, tl = e & 63;
+    const int64_t tok = tok0 + tl;
+    if (tok >= tokens) continue;
+    const int64_t b = tok / L;
+    const int t = (int)(tok - b * L);
+    flags[((size_t)b * H_f + h) * L + t] = fl[h][tl];
+  }
+}
+
+struct gate_plan {
+  int mt, tiles, splits, chunks_per_split;
+  int64_t tokens_pad;
+};
+
+gate_plan plan_gate(int64_t tokens, int d_in, ag_dtype dt, int num_cu) {
+  gate_plan p;
+  if (dt != AG_BF16) {
+    p.mt = 1; p.tiles = (int)((tokens + 7) / 8); p.splits = 1; p.chunks_per_split = 0;
+    p.tokens_pad = (tokens + 63) / 64 * 64;
+    return p;
+  }
+  const int nchunks = d_in / 64;
+  p.mt = tokens >= (int64_t)64 * 8 * num_cu ? 2 : 1;
+  p.tiles = (int)((tokens + 32 * p.mt - 1) / (32 * p.mt));
+  // enough workgroups to cover the chip about 4 times, but at least 4 chunks (one per wave) per split
+  int want = (4 * num_cu + p.tiles - 1) / p.tiles;
+  int max_splits = nchunks / 4 > 0 ? nchunks / 4 : 1;
+  p.splits = want < 1 ? 1 : (want > max_splits ? max_splits : want);
+  if (p.splits > 16) p.splits = 16;
+  p.chunks_per_split = (nchunks + p.splits - 1) / p.splits;
+  p.splits = (nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
+  p.tokens_pad = (int64_t)p.tiles * 32 * p.mt;
+  if (p.tokens_pad % 64) p.tokens_pad += 32;
+  return p;
+}
+
+}  // namespace
+
+size_t ag_ws_gate_bytes(int64_t tokens, int d_in, int H_f, ag_dtype dt) {
+  (void)H_f;
+  // worst case over the plans plan_gate can pick (num_cu is not known here): 16 splits
+  const int64_t tokens_pad = (tokens + 63) / 64 * 64;
+  const size_t part = ag_align256((size_t)16 * tokens_pad * kNP * sizeof(float));
+  const size_t pack = dt == AG_BF16 ? ag_align256((size_t)d_in * kNP * 2) : 0;
+  return part + pack;
+}
+
+hipError_t ag_launch_gate(hipStream_t s, int num_cu, const void *feat, ag_dtype dt, int B, int L, int d_in,
+                          const void *w, const float *bias, int H_f, float thr, int n_sink, float *logits,
+                          uint8_t *flags, ws_cursor &ws) {
+  const int64_t tokens = (int64_t)B * L;
+  const gate_plan p = plan_gate(tokens, d_in, dt, num_cu);
+  float *partial = ws.take<float>((size_t)p.splits * p.tokens_pad * kNP);
+  uint16_t *wp = dt == AG_BF16 ? ws.take<uint16_t>((size_t)d_in * kNP) : nullptr;
+  if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
+  if (dt == AG_BF16) {
+    const int n = d_in * kNP;
+    hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp);
+    const dim3 grid(p.tiles, p.splits);
+    if (p.mt == 2)
+      hipLaunchKernelGGL(ag_gate_mfma_kernel<2>, grid, dim3(256), 0, s, (const uint16_t *)feat, (const uint4 *)wp,
+                         tokens, d_in, p.chunks_per_split, partial, p.tokens_pad);
+    else
+      hipLaunchKernelGGL(ag_gate_mfma_kernel<1>, grid, dim3(256), 0, s, (const uint16_t *)feat, (const uint4 *)wp,
+                         tokens, d_in, p.chunks_per_split, partial, p.tokens_pad);
+  } else {
+    hipLaunchKernelGGL(ag_gate_f32_kernel, dim3(p.tiles), dim3(256), 0, s, (const float *)feat, (const float *)w,
+                       tokens, d_in, H_f, partial);
+  }
+  hipLaunchKernelGGL(ag_gate_finalize_kernel, dim3((unsigned)((tokens + 63) / 64)), dim3(256), 0, s, partial,
+                     p.splits, p.tokens_pad, tokens, L, H_f, bias, thr, n_sink, logits, flags);
+  return hipGetLastError();
+}

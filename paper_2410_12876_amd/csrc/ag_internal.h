@@ -1,0 +1,69 @@
+// Internal declarations shared by the libag translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "ag.h"
+
+struct ag_ctx {
+  int device;       // -1: no device (argument validation only)
+  int num_cu;
+  char *ws;         // device workspace
+  size_t ws_bytes;
+  int32_t *d_err;   // sticky device error word (bit 0: cache capacity overflow)
+  char err[320];
+};
+
+// Bump allocator over the context's workspace; every block is 256-byte aligned.
+struct ws_cursor {
+  char *base;
+  size_t size, off;
+  bool ok;
+  template <typename T>
+  T *take(size_t n) {
+    size_t bytes = (n * sizeof(T) + 255) & ~size_t(255);
+    if (off + bytes > size) { ok = false; off += bytes; return nullptr; }
+    T *p = reinterpret_cast<T *>(base + off);
+    off += bytes;
+    return p;
+  }
+};
+
+static inline size_t ag_align256(size_t b) { return (b + 255) & ~size_t(255); }
+static inline size_t ag_dtype_size(ag_dtype t) { return t == AG_BF16 ? 2 : 4; }
+
+ag_status ag_fail(ag_ctx *ctx, ag_status st, const char *fmt, ...);
+
+// ---- sizes of the per-call workspace blocks (host helpers, also used by ag_workspace_bytes) ----
+static inline int ag_nwords(int L) { return (L + 63) / 64; }
+size_t ag_ws_scan_bytes(int units, int L);
+size_t ag_ws_gate_bytes(int64_t tokens, int d_in, int H_f, ag_dtype dt);
+size_t ag_ws_decode_bytes(int units, int G, int D, int64_t cache_rows);
+
+// ---- kernel launchers (each enqueues on `s` and returns the launch status) ----
+// Flag scan: 64-bit keep masks per 64 tokens and their exclusive prefix counts.
+//   words [units, nw], blk_off [units, nw + 1]  (nw = ceil(L / 64)); blk_off[u][nw] = kept rows of unit u.
+hipError_t ag_launch_flag_scan(hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
+                               int32_t *blk_off);
+
+// row_off[u] = u * L for u in [0, units]: one full-length slab per unit.
+hipError_t ag_launch_slab_offsets(hipStream_t s, int64_t *row_off, int units, int L);
+
+hipError_t ag_launch_compact(hipStream_t s, const void *k, const void *v, const uint64_t *words,
+                             const int32_t *blk_off, int units, int L, int row_bytes, int pos0, void *kc, void *vc,
+                             int32_t *idx, const int64_t *row_off, int32_t *len, int32_t *d_err);
+
+hipError_t ag_launch_gate(hipStream_t s, int num_cu, const void *feat, ag_dtype dt, int B, int L, int d_in,
+                          const void *w, const float *bias, int H_f, float thr, int n_sink, float *logits,
+                          uint8_t *flags, ws_cursor &ws);
+
+hipError_t ag_launch_prefill(hipStream_t s, int num_cu, const void *q, const void *k, const void *v,
+                             const uint64_t *words, const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D,
+                             ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
+                             void *out);
+
+hipError_t ag_launch_decode(hipStream_t s, int num_cu, const void *q, const void *k_new, const void *v_new,
+                            const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
+                            float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
+                            int64_t total_rows, void *out, int32_t *d_err, ws_cursor &ws);
