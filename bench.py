@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the Attention-Gate hot path on one MI355X.
+
+One "step" is one pass of the whole path over one Llama2-7B-shaped layer (config 2: bf16, B=1, L=4096,
+d=4096, 32 heads x 128, per-head keep ratios U[0.2, 0.9]):
+    ag_gate -> ag_compact_kv -> ag_prefill_attn (over the compacted cache) -> one ag_decode_attn step.
+`value` is prompt tokens per second through that step, inputs resident in HBM.  The same JSON line carries
+  roofline      : the dominant kernel (masked prefill attention) against the bf16 MFMA peak,
+  decode        : config 3 (B=32, ragged caches ~ round(4096 U[0.1,1]), Bernoulli(0.5) appends), 256 decode
+                  steps, achieved HBM GB/s of the decode kernel against the 8 TB/s peak,
+  cpu_baseline  : the CPU oracle timed on a bounded sample of the same workload on the host cores.
+Kernel durations come from HIP events recorded around each kernel on the launch stream inside the timed
+region (ag_timing_* of the C ABI).
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def to_dev(t, torch):
+    if t.is_bf16:
+        return torch.from_numpy(t.bits.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(t.f32).cuda()
+
+
+def visible_pairs(flags: np.ndarray, G: int) -> int:
+    """sum over (b, query head, row j) of (cnt[j] + 1): visible query-key pairs incl. the diagonal."""
+    f = flags.astype(np.int64)
+    cnt = np.cumsum(f, axis=-1) - f          # exclusive prefix count
+    return int((cnt + 1).sum()) * G
+
+
+def prefill_leg(args, torch, ag, W):
+    wl = W.config2(L=args.seq_len)
+    B, L, Hq, Hkv, D, d = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D, wl.d_model
+    G = Hq // Hkv
+    U = B * Hkv
+    cap = L + 8
+    rows = U * cap
+    ctx = ag.Context(0, ag.workspace_bytes(B, L, Hq, Hkv, D, ag.AG_BF16, d, rows))
+    x, wg, bias = to_dev(wl.x, torch), to_dev(wl.w_gate, torch), torch.from_numpy(wl.bias).cuda()
+    q, k, v = to_dev(wl.q, torch), to_dev(wl.k, torch), to_dev(wl.v, torch)
+    flags = torch.empty(B, Hkv, L, dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(q)
+    ro = np.arange(U + 1, dtype=np.int64) * cap
+    cache = ag.KVCache(torch.zeros(rows, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(rows, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(rows, dtype=torch.int32, device="cuda"), torch.from_numpy(ro).cuda(),
+                       torch.zeros(U, dtype=torch.int32, device="cuda"), B, Hkv, D)
+    dq = torch.randn(B, Hq, D, device="cuda").to(torch.bfloat16)
+    dk = torch.randn(B, Hkv, D, device="cuda").to(torch.bfloat16)
+    dv = torch.randn(B, Hkv, D, device="cuda").to(torch.bfloat16)
+    dout = torch.empty_like(dq)
+
+    def step():
+        ag.ag_gate(ctx, x, wg, bias, wl.tau, wl.n_sink, None, flags)
+        ag.ag_compact_kv(ctx, k, v, flags, 0, cache)
+        ag.ag_prefill_attn(ctx, q, k, v, flags, wl.scale, cache, out)
+        ag.ag_decode_attn(ctx, dq, dk, dv, None, L, wl.scale, cache, dout)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    times = ctx.timing_read()
+    ctx.timing_enable(False)
+    ctx.poll_error()
+
+    fl = flags.cpu().numpy()
+    pairs = visible_pairs(fl, G)
+    flops = 4.0 * D * pairs
+    kept_rows = int(fl.sum())
+    per_kernel = {n: (ms / c if c else None) for n, (ms, c) in times.items()}
+    pf_ms = per_kernel["prefill"]
+    ach = flops / (pf_ms * 1e-3) / 1e12
+    res = {
+        "seconds": t1 - t0,
+        "tokens": B * L * args.steps,
+        "kernel_ms": per_kernel,
+        "keep_ratio": float(fl.mean()),
+        "roofline": {"kernel": "ag_prefill_mfma_kernel<128,1>", "bound": "mfma", "achieved": ach,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "flops_per_launch": flops, "visible_pairs": pairs,
+                     "avg_launch_ms": pf_ms},
+        "compact_gbs": (2 * 2 * kept_rows * D * 2 + fl.size + 4 * kept_rows) / (per_kernel["compact"] * 1e-3) / 1e9,
+        "gate_gbs": (B * L * d * 2) / (per_kernel["gate"] * 1e-3) / 1e9,
+        "config": {"workload": wl.name, "B": B, "L": L, "d_model": d, "Hq": Hq, "Hkv": Hkv, "D": D,
+                   "keep": "per-head U[0.2,0.9], mean %.3f" % fl.mean()},
+    }
+    ctx.close()
+    return res, wl, fl
+
+
+def decode_leg(args, torch, ag, W):
+    steps, warm = args.decode_steps, min(args.warmup, 8)
+    wl = W.config3(B=args.decode_batch, steps=steps + warm)
+    B, Hq, Hkv, D = wl.B, wl.Hq, wl.Hkv, wl.D
+    total = int(wl.row_off[-1])
+    ctx = ag.Context(0, ag.workspace_bytes(B, 1, Hq, Hkv, D, ag.AG_BF16, 0, total))
+    cache = ag.KVCache(to_dev(wl.k_cache, torch), to_dev(wl.v_cache, torch), torch.from_numpy(wl.idx).cuda(),
+                       torch.from_numpy(wl.row_off).cuda(), torch.from_numpy(wl.len0).cuda(), B, Hkv, D,
+                       total_rows=total)
+    n_in = 8
+    ins = []
+    for s in range(n_in):
+        q, kn, vn, nf = wl.step_inputs(s, 0.5)
+        ins.append((to_dev(q, torch), to_dev(kn, torch), to_dev(vn, torch), torch.from_numpy(nf).cuda()))
+    out = torch.empty(B, Hq, D, dtype=torch.bfloat16, device="cuda")
+
+    def step(s):
+        q, kn, vn, nf = ins[s % n_in]
+        ag.ag_decode_attn(ctx, q, kn, vn, nf, wl.pos0 + s, wl.scale, cache, out)
+
+    for s in range(warm):
+        step(s)
+    torch.cuda.synchronize()
+    len_before = cache.len.cpu().numpy().astype(np.int64)
+    ctx.timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(warm, warm + steps):
+        step(s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    times = ctx.timing_read()
+    ctx.timing_enable(False)
+    ctx.poll_error()
+    len_after = cache.len.cpu().numpy().astype(np.int64)
+    # rows read per step grow by the appends; appends are spread evenly, so use the mean of first and last
+    rows_per_step = 0.5 * (len_before.sum() + len_after.sum())
+    bytes_per_step = rows_per_step * D * 2 * 2
+    part_ms = times["decode_partial"][0] / max(times["decode_partial"][1], 1)
+    merge_ms = times["decode_merge"][0] / max(times["decode_merge"][1], 1)
+    ach = bytes_per_step / (part_ms * 1e-3) / 1e9
+    res = {
+        "metric": "decode attention HBM GB/s", "value": bytes_per_step * steps / (t1 - t0) / 1e9, "unit": "GB/s",
+        "steps": steps, "ms_per_step": (t1 - t0) / steps * 1e3,
+        "kernel_ms": {"decode_partial": part_ms, "decode_merge": merge_ms},
+        "roofline": {"kernel": "ag_decode_partial_kernel<bf16,128,1>", "bound": "hbm", "achieved": ach,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": bytes_per_step, "avg_launch_ms": part_ms},
+        "config": {"workload": wl.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D,
+                   "mean_len": float(rows_per_step / (B * Hkv)), "keep_vs_4096": float(rows_per_step / (B * Hkv) / 4096)},
+    }
+    ctx.close()
+    return res, wl
+
+
+def cpu_baseline(wl, flags, W):
+    """The oracle on a bounded sample: the whole step for 8 of the 32 heads (gate over all tokens for those
+    heads' columns, compaction, masked prefill, one decode step), scaled to the full layer."""
+    import oracle
+    hs = list(range(0, wl.Hkv, wl.Hkv // 8))[:8]
+    L, D = wl.L, wl.D
+    x, wg, bias = wl.x.f32, np.ascontiguousarray(wl.w_gate.f32[:, hs]), wl.bias[hs]
+    q, k, v = (np.ascontiguousarray(t.f32[:, hs]) for t in (wl.q, wl.k, wl.v))
+    kb, vb = np.ascontiguousarray(wl.k.bits[:, hs]), np.ascontiguousarray(wl.v.bits[:, hs])
+    ro = oracle.slab_row_off(len(hs), L + 8)
+    g = np.random.default_rng(0)
+    dq, dk, dv = (g.standard_normal((1, len(hs), D)).astype(np.float32) for _ in range(3))
+    t0 = time.perf_counter()
+    _, f = oracle.gate(x, wg, bias, wl.tau, wl.n_sink)
+    oracle.compact_kv(kb, vb, f, ro)
+    oracle.prefill_attn(q, k, v, f, wl.scale)
+    t_mid = time.perf_counter()
+    c32, _ = oracle.compact_kv(k, v, f, ro)
+    t_mid2 = time.perf_counter()
+    oracle.decode_step(dq, dk, dv, None, L, c32, wl.scale)
+    t1 = time.perf_counter()
+    t = (t_mid - t0) + (t1 - t_mid2)
+    scale_up = wl.Hkv / len(hs)
+    return {"value": wl.B * L / (t * scale_up), "unit": "tokens/s", "cores": min(oracle.threads(), len(hs)),
+            "kind": "oracle", "sample": "whole step (gate, compaction, masked prefill, 1 decode step) for heads %s of %d; "
+            "%.2f s measured, scaled by %g" % (hs, wl.Hkv, t, scale_up), "seconds_sample": t}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--seq-len", type=int, default=4096)
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--decode-batch", type=int, default=32)
+    ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2410_12876_amd as ag
+    import workloads as W
+    if not os.path.exists(ag.LIB_PATH):
+        from paper_2410_12876_amd import build
+        build.build()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    log("[bench] generating config 2 ...")
+    pre, wl, flags = prefill_leg(args, torch, ag, W)
+    log("[bench] prefill leg done: %.3f ms/step" % (pre["seconds"] / args.steps * 1e3))
+    dec = None
+    if not args.skip_decode:
+        log("[bench] generating config 3 ...")
+        dec, _ = decode_leg(args, torch, ag, W)
+        log("[bench] decode leg done: %.1f GB/s" % dec["value"])
+    cpu = None
+    if not args.skip_cpu_baseline:
+        log("[bench] timing the CPU oracle on a sample ...")
+        cpu = cpu_baseline(wl, flags, W)
+
+    line = {
+        "metric": "prefill tokens/s (gate + compaction + masked prefill attention + 1 decode step per layer)",
+        "value": pre["tokens"] / pre["seconds"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": pre["seconds"] / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": pre["config"], "kernel_ms": pre["kernel_ms"], "roofline": pre["roofline"],
+        "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -79,6 +79,18 @@ size_t ag_workspace_bytes(int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, 
 ag_status ag_poll_error(ag_ctx *ctx, void *hip_stream);
 
 /*
+ * Kernel timing for benchmarks.  While enabled, every kernel the library launches is bracketed by a pair of
+ * HIP events on the call's stream (up to 1024 launches per kernel id are remembered; later ones are not
+ * timed).  ag_timing_enable(ctx, 1) resets the counts; ag_timing_read waits for the recorded events and
+ * returns the summed duration and the number of launches of one kernel id in [0, ag_timing_kernels()).
+ * Ids: 0 gate (GEMM), 1 gate_finalize, 2 flag_scan, 3 compact, 4 prefill, 5 decode_partial, 6 decode_merge.
+ */
+int ag_timing_kernels(void);
+const char *ag_timing_kernel_name(int kernel_id);
+ag_status ag_timing_enable(ag_ctx *ctx, int on);
+ag_status ag_timing_read(ag_ctx *ctx, int kernel_id, double *total_ms, int *launches);
+
+/*
  * Gate (Eq. 3 and Eq. 4; the constant inside the sigmoid is Sec. 3.5 "Initialization").
  *   logit[b,t,h] = sum_c feat[b,t,c] * w_gate[c,h] + bias[h]          (fp32 accumulate)
  *   flag [b,h,t] = Sigmoid(logit) > tau  <=>  logit > ln(tau/(1-tau))   (strict; compared in fp32)

@@ -19,7 +19,7 @@ AG_F32, AG_BF16 = 0, 1
 STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWORKSPACE", "AG_EHIP"]
 
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
-           "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_decode_attn"]
+           "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_decode_attn"]
 
 
 class AgError(RuntimeError):
@@ -57,6 +57,13 @@ def load() -> C.CDLL:
     lib.ag_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32, i64]
     lib.ag_poll_error.restype = C.c_int
     lib.ag_poll_error.argtypes = [vp, vp]
+    lib.ag_timing_kernels.restype = C.c_int
+    lib.ag_timing_kernel_name.restype = C.c_char_p
+    lib.ag_timing_kernel_name.argtypes = [i32]
+    lib.ag_timing_enable.restype = C.c_int
+    lib.ag_timing_enable.argtypes = [vp, i32]
+    lib.ag_timing_read.restype = C.c_int
+    lib.ag_timing_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.ag_gate.restype = C.c_int
     lib.ag_gate.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, f32, i32, vp, vp]
     lib.ag_compact_kv.restype = C.c_int
@@ -129,6 +136,18 @@ class Context:
 
     def poll_error(self, stream=None) -> None:
         self._check(self._lib.ag_poll_error(self._h, _stream_ptr(stream)))
+
+    def timing_enable(self, on: bool = True) -> None:
+        self._check(self._lib.ag_timing_enable(self._h, 1 if on else 0))
+
+    def timing_read(self) -> dict:
+        """{kernel name: (total ms, launches)} of the launches recorded since timing_enable(True)."""
+        out = {}
+        for kid in range(self._lib.ag_timing_kernels()):
+            ms, n = C.c_double(), C.c_int()
+            self._check(self._lib.ag_timing_read(self._h, kid, C.byref(ms), C.byref(n)))
+            out[self._lib.ag_timing_kernel_name(kid).decode()] = (ms.value, n.value)
+        return out
 
 
 class KVCache:

@@ -99,9 +99,70 @@ void ag_destroy(ag_ctx *ctx) {
   if (!ctx) return;
   if (ctx->device >= 0 && ctx->ws) {
     (void)hipSetDevice(ctx->device);
+    for (int id = 0; id < AG_K_COUNT; ++id) {
+      ag_timer &t = ctx->timers[id];
+      if (!t.start) continue;
+      for (int i = 0; i < kTimerSlots; ++i) {
+        (void)hipEventDestroy(t.start[i]);
+        (void)hipEventDestroy(t.stop[i]);
+      }
+      delete[] t.start;
+      delete[] t.stop;
+    }
     (void)hipFree(ctx->ws);
   }
   delete ctx;
+}
+
+static const char *const kKernelNames[AG_K_COUNT] = {"gate", "gate_finalize", "flag_scan", "compact",
+                                                     "prefill", "decode_partial", "decode_merge"};
+
+int ag_timing_kernels(void) { return AG_K_COUNT; }
+
+const char *ag_timing_kernel_name(int kernel_id) {
+  return kernel_id >= 0 && kernel_id < AG_K_COUNT ? kKernelNames[kernel_id] : "";
+}
+
+ag_status ag_timing_enable(ag_ctx *ctx, int on) {
+  if (!ctx) return AG_EINVAL;
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  if (on) {
+    for (int id = 0; id < AG_K_COUNT; ++id) {
+      ag_timer &t = ctx->timers[id];
+      if (!t.start) {
+        t.start = new (std::nothrow) hipEvent_t[kTimerSlots];
+        t.stop = new (std::nothrow) hipEvent_t[kTimerSlots];
+        if (!t.start || !t.stop) return ag_fail(ctx, AG_EHIP, "ag_timing_enable: out of host memory");
+        for (int i = 0; i < kTimerSlots; ++i) {
+          AG_HIP(hipEventCreate(&t.start[i]));
+          AG_HIP(hipEventCreate(&t.stop[i]));
+        }
+      }
+      t.n = 0;
+    }
+  }
+  ctx->timing = on != 0;
+  return AG_OK;
+}
+
+ag_status ag_timing_read(ag_ctx *ctx, int kernel_id, double *total_ms, int *launches) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(kernel_id >= 0 && kernel_id < AG_K_COUNT && total_ms && launches, AG_EINVAL,
+             "ag_timing_read: bad kernel id or null pointer");
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  const ag_timer &t = ctx->timers[kernel_id];
+  double sum = 0.0;
+  for (int i = 0; i < t.n; ++i) {
+    float ms = 0.f;
+    AG_HIP(hipEventSynchronize(t.stop[i]));
+    AG_HIP(hipEventElapsedTime(&ms, t.start[i], t.stop[i]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = t.n;
+  return AG_OK;
 }
 
 const char *ag_last_error(const ag_ctx *ctx) { return ctx ? ctx->err : "null context"; }
@@ -156,7 +217,7 @@ ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtyp
   if (st != AG_OK) return st;
   const float thr = (float)log((double)tau / (1.0 - (double)tau));
   ws_cursor ws = cursor(ctx);
-  hipError_t e = ag_launch_gate((hipStream_t)hip_stream, ctx->num_cu, feat, dtype, B, L, d_in, w_gate, bias, H_f, thr,
+  hipError_t e = ag_launch_gate(ctx, (hipStream_t)hip_stream, feat, dtype, B, L, d_in, w_gate, bias, H_f, thr,
                                 n_sink, logits_out, flags_out, ws);
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_gate: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes, ws.off);
   AG_HIP(e);
@@ -182,9 +243,9 @@ ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void
   int32_t *blk_off = ws.take<int32_t>((size_t)units * (nw + 1));
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_compact_kv: workspace too small (need %zu)", ws.off);
   hipStream_t s = (hipStream_t)hip_stream;
-  AG_HIP(ag_launch_flag_scan(s, flags, units, L, words, blk_off));
-  AG_HIP(ag_launch_compact(s, k, v, words, blk_off, units, L, (int)(cache->D * ag_dtype_size(cache->dtype)), pos0,
-                           cache->k, cache->v, cache->idx, cache->row_off, cache->len, ctx->d_err));
+  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off));
+  AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(cache->D * ag_dtype_size(cache->dtype)), pos0,
+                           cache->k, cache->v, cache->idx, cache->row_off, cache->len));
   return AG_OK;
 }
 
@@ -233,13 +294,12 @@ ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const vo
   ag_status st = need_device(ctx);
   if (st != AG_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
-  AG_HIP(ag_launch_flag_scan(s, flags, units, L, words, blk_off));
+  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off));
   if (!cache) {
     AG_HIP(ag_launch_slab_offsets(s, wro, units, L));
-    AG_HIP(ag_launch_compact(s, k, v, words, blk_off, units, L, (int)(D * esz), 0, wk, wv, widx, wro, wlen,
-                             ctx->d_err));
+    AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(D * esz), 0, wk, wv, widx, wro, wlen));
   }
-  AG_HIP(ag_launch_prefill(s, ctx->num_cu, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, kc, vc, row_off,
+  AG_HIP(ag_launch_prefill(ctx, s, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, kc, vc, row_off,
                            out));
   return AG_OK;
 }
@@ -260,9 +320,9 @@ ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const voi
   st = need_device(ctx);
   if (st != AG_OK) return st;
   ws_cursor ws = cursor(ctx);
-  hipError_t e = ag_launch_decode((hipStream_t)hip_stream, ctx->num_cu, q, k_new, v_new, new_flags, pos, cache->B, Hq,
-                                  cache->Hkv, cache->D, cache->dtype, scale, cache->k, cache->v, cache->idx,
-                                  cache->row_off, cache->len, cache->total_rows, out, ctx->d_err, ws);
+  hipError_t e = ag_launch_decode(ctx, (hipStream_t)hip_stream, q, k_new, v_new, new_flags, pos, cache->B, Hq, cache->Hkv,
+                                  cache->D, cache->dtype, scale, cache->k, cache->v, cache->idx, cache->row_off,
+                                  cache->len, cache->total_rows, out, ws);
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_decode_attn: workspace too small (need %zu)", ws.off);
   AG_HIP(e);
   return AG_OK;

@@ -134,27 +134,32 @@ size_t ag_ws_scan_bytes(int units, int L) {
   return ag_align256((size_t)units * nw * sizeof(uint64_t)) + ag_align256((size_t)units * (nw + 1) * sizeof(int32_t));
 }
 
-hipError_t ag_launch_flag_scan(hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
+hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
                                int32_t *blk_off) {
   const int nw = ag_nwords(L);
   const size_t shmem = (size_t)(nw + kScanThreads) * sizeof(int32_t);
+  ag_tick(ctx, AG_K_FLAG_SCAN, s);
   hipLaunchKernelGGL(ag_flag_scan_kernel, dim3(units), dim3(kScanThreads), shmem, s, flags, L, nw, words, blk_off);
+  ag_tock(ctx, AG_K_FLAG_SCAN, s);
   return hipGetLastError();
 }
 
-hipError_t ag_launch_compact(hipStream_t s, const void *k, const void *v, const uint64_t *words,
+hipError_t ag_launch_compact(ag_ctx *ctx, hipStream_t s, const void *k, const void *v, const uint64_t *words,
                              const int32_t *blk_off, int units, int L, int row_bytes, int pos0, void *kc, void *vc,
-                             int32_t *idx, const int64_t *row_off, int32_t *len, int32_t *d_err) {
+                             int32_t *idx, const int64_t *row_off, int32_t *len) {
+  int32_t *d_err = ctx->d_err;
   const int nw = ag_nwords(L);
   const int row_vec = row_bytes / 16;
   const dim3 grid((nw + 3) / 4, units), block(256);
 #define AG_COMPACT(LPR)                                                                                           \
   hipLaunchKernelGGL(ag_compact_kernel<LPR>, grid, block, 0, s, (const uint4 *)k, (const uint4 *)v, words, blk_off, \
                      nw, L, row_vec, pos0, (uint4 *)kc, (uint4 *)vc, idx, row_off, len, d_err)
+  ag_tick(ctx, AG_K_COMPACT, s);
   if (row_vec <= 8) AG_COMPACT(8);
   else if (row_vec <= 16) AG_COMPACT(16);
   else if (row_vec <= 32) AG_COMPACT(32);
   else AG_COMPACT(64);
 #undef AG_COMPACT
+  ag_tock(ctx, AG_K_COMPACT, s);
   return hipGetLastError();
 }

@@ -291,10 +291,11 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
 int64_t max_items(int units, int64_t cache_rows) { return cache_rows / kChunk + units; }
 
 template <typename T, int D, int G>
-hipError_t launch_t(hipStream_t s, int num_cu, const void *q, const void *k_new, const void *v_new,
+hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                     const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, float scale, void *kc, void *vc,
-                    int32_t *idx, const int64_t *row_off, int32_t *len, int64_t total_rows, void *out, int32_t *d_err,
-                    ws_cursor &ws) {
+                    int32_t *idx, const int64_t *row_off, int32_t *len, int64_t total_rows, void *out, ws_cursor &ws) {
+  const int num_cu = ctx->num_cu;
+  int32_t *d_err = ctx->d_err;
   const int U = B * Hkv;
   const int64_t items = max_items(U, total_rows);
   int32_t *item_off = ws.take<int32_t>(U + 1);
@@ -313,11 +314,15 @@ hipError_t launch_t(hipStream_t s, int num_cu, const void *q, const void *k_new,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
   }
+  ag_tick(ctx, AG_K_DECODE_PARTIAL, s);
   hipLaunchKernelGGL((ag_decode_partial_kernel<T, D, G>), dim3(blocks), dim3(256), shmem, s, (const T *)q,
                      (const T *)kc, (const T *)vc, row_off, len, U, Hkv, qscale, item_off, pm, pl, pacc);
+  ag_tock(ctx, AG_K_DECODE_PARTIAL, s);
+  ag_tick(ctx, AG_K_DECODE_MERGE, s);
   hipLaunchKernelGGL((ag_decode_merge_kernel<T, D>), dim3(B * Hq), dim3(D), 0, s, (const T *)q, (const T *)k_new,
                      (const T *)v_new, new_flags, pos, Hq, Hkv, qscale, item_off, pm, pl, pacc, (T *)kc, (T *)vc, idx,
                      row_off, len, (T *)out, d_err);
+  ag_tock(ctx, AG_K_DECODE_MERGE, s);
   return hipGetLastError();
 }
 
@@ -346,14 +351,14 @@ bool ag_decode_supported(ag_dtype dt, int D, int G, int units) {
   return dt == AG_BF16 ? (D == 64 || D == 128) : (D == 64 || D == 128);
 }
 
-hipError_t ag_launch_decode(hipStream_t s, int num_cu, const void *q, const void *k_new, const void *v_new,
+hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
                             float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
-                            int64_t total_rows, void *out, int32_t *d_err, ws_cursor &ws) {
+                            int64_t total_rows, void *out, ws_cursor &ws) {
   const int G = Hq / Hkv;
 #define AG_DEC(T, DD)                                                                                              \
-  return launch_g<T, DD>(G, s, num_cu, q, k_new, v_new, new_flags, pos, B, Hq, Hkv, scale, kc, vc, idx, row_off, len, \
-                         total_rows, out, d_err, ws)
+  return launch_g<T, DD>(G, ctx, s, q, k_new, v_new, new_flags, pos, B, Hq, Hkv, scale, kc, vc, idx, row_off, len, \
+                         total_rows, out, ws)
   if (dt == AG_BF16) {
     if (D == 64) AG_DEC(uint16_t, 64);
     if (D == 128) AG_DEC(uint16_t, 128);

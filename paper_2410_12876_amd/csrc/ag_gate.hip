@@ -164,11 +164,11 @@ size_t ag_ws_gate_bytes(int64_t tokens, int d_in, int H_f, ag_dtype dt) {
   return part + pack;
 }
 
-hipError_t ag_launch_gate(hipStream_t s, int num_cu, const void *feat, ag_dtype dt, int B, int L, int d_in,
+hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype dt, int B, int L, int d_in,
                           const void *w, const float *bias, int H_f, float thr, int n_sink, float *logits,
                           uint8_t *flags, ws_cursor &ws) {
   const int64_t tokens = (int64_t)B * L;
-  const gate_plan p = plan_gate(tokens, d_in, dt, num_cu);
+  const gate_plan p = plan_gate(tokens, d_in, dt, ctx->num_cu);
   float *partial = ws.take<float>((size_t)p.splits * p.tokens_pad * kNP);
   uint16_t *wp = dt == AG_BF16 ? ws.take<uint16_t>((size_t)d_in * kNP) : nullptr;
   if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
@@ -176,17 +176,23 @@ hipError_t ag_launch_gate(hipStream_t s, int num_cu, const void *feat, ag_dtype 
     const int n = d_in * kNP;
     hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp);
     const dim3 grid(p.tiles, p.splits);
+    ag_tick(ctx, AG_K_GATE, s);
     if (p.mt == 2)
       hipLaunchKernelGGL(ag_gate_mfma_kernel<2>, grid, dim3(256), 0, s, (const uint16_t *)feat, (const uint4 *)wp,
                          tokens, d_in, p.chunks_per_split, partial, p.tokens_pad);
     else
       hipLaunchKernelGGL(ag_gate_mfma_kernel<1>, grid, dim3(256), 0, s, (const uint16_t *)feat, (const uint4 *)wp,
                          tokens, d_in, p.chunks_per_split, partial, p.tokens_pad);
+    ag_tock(ctx, AG_K_GATE, s);
   } else {
+    ag_tick(ctx, AG_K_GATE, s);
     hipLaunchKernelGGL(ag_gate_f32_kernel, dim3(p.tiles), dim3(256), 0, s, (const float *)feat, (const float *)w,
                        tokens, d_in, H_f, partial);
+    ag_tock(ctx, AG_K_GATE, s);
   }
+  ag_tick(ctx, AG_K_GATE_FINALIZE, s);
   hipLaunchKernelGGL(ag_gate_finalize_kernel, dim3((unsigned)((tokens + 63) / 64)), dim3(256), 0, s, partial,
                      p.splits, p.tokens_pad, tokens, L, H_f, bias, thr, n_sink, logits, flags);
+  ag_tock(ctx, AG_K_GATE_FINALIZE, s);
   return hipGetLastError();
 }

@@ -6,14 +6,37 @@
 
 #include "ag.h"
 
+// Kernels that ag_timing_* can time (ids are part of the ABI, see ag.h).
+enum { AG_K_GATE = 0, AG_K_GATE_FINALIZE, AG_K_FLAG_SCAN, AG_K_COMPACT, AG_K_PREFILL, AG_K_DECODE_PARTIAL,
+       AG_K_DECODE_MERGE, AG_K_COUNT };
+constexpr int kTimerSlots = 1024;  // launches remembered per kernel id
+
+struct ag_timer {
+  hipEvent_t *start, *stop;  // kTimerSlots each, created on first enable
+  int n;                     // launches recorded since the last enable
+};
+
 struct ag_ctx {
   int device;       // -1: no device (argument validation only)
   int num_cu;
   char *ws;         // device workspace
   size_t ws_bytes;
   int32_t *d_err;   // sticky device error word (bit 0: cache capacity overflow)
+  bool timing;
+  ag_timer timers[AG_K_COUNT];
   char err[320];
 };
+
+// Event pair around one kernel launch when timing is on (no-ops otherwise).
+static inline void ag_tick(ag_ctx *ctx, int id, hipStream_t s) {
+  if (ctx->timing && ctx->timers[id].n < kTimerSlots) (void)hipEventRecord(ctx->timers[id].start[ctx->timers[id].n], s);
+}
+static inline void ag_tock(ag_ctx *ctx, int id, hipStream_t s) {
+  if (ctx->timing && ctx->timers[id].n < kTimerSlots) {
+    (void)hipEventRecord(ctx->timers[id].stop[ctx->timers[id].n], s);
+    ctx->timers[id].n++;
+  }
+}
 
 // Bump allocator over the context's workspace; every block is 256-byte aligned.
 struct ws_cursor {
@@ -44,26 +67,26 @@ size_t ag_ws_decode_bytes(int units, int G, int D, int64_t cache_rows);
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----
 // Flag scan: 64-bit keep masks per 64 tokens and their exclusive prefix counts.
 //   words [units, nw], blk_off [units, nw + 1]  (nw = ceil(L / 64)); blk_off[u][nw] = kept rows of unit u.
-hipError_t ag_launch_flag_scan(hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
+hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
                                int32_t *blk_off);
 
 // row_off[u] = u * L for u in [0, units]: one full-length slab per unit.
 hipError_t ag_launch_slab_offsets(hipStream_t s, int64_t *row_off, int units, int L);
 
-hipError_t ag_launch_compact(hipStream_t s, const void *k, const void *v, const uint64_t *words,
+hipError_t ag_launch_compact(ag_ctx *ctx, hipStream_t s, const void *k, const void *v, const uint64_t *words,
                              const int32_t *blk_off, int units, int L, int row_bytes, int pos0, void *kc, void *vc,
-                             int32_t *idx, const int64_t *row_off, int32_t *len, int32_t *d_err);
+                             int32_t *idx, const int64_t *row_off, int32_t *len);
 
-hipError_t ag_launch_gate(hipStream_t s, int num_cu, const void *feat, ag_dtype dt, int B, int L, int d_in,
+hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype dt, int B, int L, int d_in,
                           const void *w, const float *bias, int H_f, float thr, int n_sink, float *logits,
                           uint8_t *flags, ws_cursor &ws);
 
-hipError_t ag_launch_prefill(hipStream_t s, int num_cu, const void *q, const void *k, const void *v,
+hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const void *k, const void *v,
                              const uint64_t *words, const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D,
                              ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
                              void *out);
 
-hipError_t ag_launch_decode(hipStream_t s, int num_cu, const void *q, const void *k_new, const void *v_new,
+hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
                             float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
-                            int64_t total_rows, void *out, int32_t *d_err, ws_cursor &ws);
+                            int64_t total_rows, void *out, ws_cursor &ws);

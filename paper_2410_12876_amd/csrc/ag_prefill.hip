@@ -294,12 +294,12 @@ bool ag_prefill_supported(ag_dtype dt, int D, int G) {
   return dt == AG_BF16 ? (D == 64 || D == 128) : (D == 32 || D == 64 || D == 128 || D == 256);
 }
 
-hipError_t ag_launch_prefill(hipStream_t s, int num_cu, const void *q, const void *k, const void *v,
+hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const void *k, const void *v,
                              const uint64_t *words, const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D,
                              ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
                              void *out) {
-  (void)num_cu;
   const int nw = ag_nwords(L);
+  ag_tick(ctx, AG_K_PREFILL, s);
   const int G = Hq / Hkv;
   const float qscale = scale * kLog2e;
   if (dt == AG_BF16) {
@@ -325,5 +325,6 @@ hipError_t ag_launch_prefill(hipStream_t s, int num_cu, const void *q, const voi
     if (D == 32) AG_PF32(32); else if (D == 64) AG_PF32(64); else if (D == 128) AG_PF32(128); else AG_PF32(256);
 #undef AG_PF32
   }
+  ag_tock(ctx, AG_K_PREFILL, s);
   return hipGetLastError();
 }
