@@ -86,6 +86,11 @@ hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const vo
                              ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
                              void *out);
 
+// bf16, D = 128: the tuned kernel of ag_prefill_d128.hip (qscale = scale * log2 e)
+hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
+                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, const void *kc,
+                                  const void *vc, const int64_t *row_off, void *out);
+
 hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
                             float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,

@@ -302,6 +302,11 @@ hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const vo
   ag_tick(ctx, AG_K_PREFILL, s);
   const int G = Hq / Hkv;
   const float qscale = scale * kLog2e;
+  if (dt == AG_BF16 && D == 128) {
+    const hipError_t e = ag_launch_prefill_d128(s, q, k, v, words, blk_off, B, L, Hq, Hkv, qscale, kc, vc, row_off, out);
+    ag_tock(ctx, AG_K_PREFILL, s);
+    return e;
+  }
   if (dt == AG_BF16) {
     const int GB = G >= 4 ? 4 : G;
     const int BM = 32 * (4 / GB);
