@@ -91,6 +91,15 @@ ag_status ag_timing_enable(ag_ctx *ctx, int on);
 ag_status ag_timing_read(ag_ctx *ctx, int kernel_id, double *total_ms, int *launches);
 
 /*
+ * Machine probes for benchmarks (no part of the attention path).  ag_probe_mfma runs a register-only loop of
+ * `iters` x 4 v_mfma_f32_32x32x16_bf16 per wave on 8 waves per CU and returns the sustained TFLOP/s;
+ * ag_probe_copy streams `bytes` (>= 4096) from one half of the context's workspace to the other, four times,
+ * and returns read+write GB/s.  Both synchronise on their own events.
+ */
+ag_status ag_probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, double *tflops);
+ag_status ag_probe_copy(ag_ctx *ctx, void *hip_stream, size_t bytes, double *gbs);
+
+/*
  * Gate (Eq. 3 and Eq. 4; the constant inside the sigmoid is Sec. 3.5 "Initialization").
  *   logit[b,t,h] = sum_c feat[b,t,c] * w_gate[c,h] + bias[h]          (fp32 accumulate)
  *   flag [b,h,t] = Sigmoid(logit) > tau  <=>  logit > ln(tau/(1-tau))   (strict; compared in fp32)

@@ -19,7 +19,8 @@ AG_F32, AG_BF16 = 0, 1
 STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWORKSPACE", "AG_EHIP"]
 
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
-           "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_decode_attn"]
+           "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
+           "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_decode_attn"]
 
 
 class AgError(RuntimeError):
@@ -64,6 +65,10 @@ def load() -> C.CDLL:
     lib.ag_timing_enable.argtypes = [vp, i32]
     lib.ag_timing_read.restype = C.c_int
     lib.ag_timing_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int)]
+    lib.ag_probe_mfma.restype = C.c_int
+    lib.ag_probe_mfma.argtypes = [vp, vp, i32, C.POINTER(C.c_double)]
+    lib.ag_probe_copy.restype = C.c_int
+    lib.ag_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double)]
     lib.ag_gate.restype = C.c_int
     lib.ag_gate.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, f32, i32, vp, vp]
     lib.ag_compact_kv.restype = C.c_int
@@ -148,6 +153,19 @@ class Context:
             self._check(self._lib.ag_timing_read(self._h, kid, C.byref(ms), C.byref(n)))
             out[self._lib.ag_timing_kernel_name(kid).decode()] = (ms.value, n.value)
         return out
+
+
+    def probe_mfma(self, iters: int = 20000, stream=None) -> float:
+        """Sustained dense bf16 MFMA TFLOP/s of this GPU (register-only loop)."""
+        out = C.c_double()
+        self._check(self._lib.ag_probe_mfma(self._h, _stream_ptr(stream), iters, C.byref(out)))
+        return out.value
+
+    def probe_copy(self, nbytes: int, stream=None) -> float:
+        """Sustained HBM read+write GB/s of a streaming copy of nbytes inside the workspace."""
+        out = C.c_double()
+        self._check(self._lib.ag_probe_copy(self._h, _stream_ptr(stream), nbytes, C.byref(out)))
+        return out.value
 
 
 class KVCache:

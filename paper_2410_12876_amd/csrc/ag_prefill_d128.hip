@@ -60,7 +60,8 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
 
   const int G = Hq / Hkv;
   const int HB = G / GB;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar, so that LDS bases stay in SGPRs
   const int col = lane & 31, hb = lane >> 5;
   // workgroup id -> (query tile, unit/head block): heads vary fastest so that a head keeps its XCD
   const int n_qt = (L + BM - 1) / BM;
@@ -88,18 +89,29 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   const uint16_t *Vc = vc + (size_t)row_off[u] * D;
 
   // ---- tile loader: wave w fills rows [16w, 16w+16) of the K and V tiles, 4 rows (1 KiB) per instruction ----
-  // lane -> (row r = 16w + 4i + lane/16, physical chunk p = lane%16); it fetches logical chunk p ^ swz(r)
+  // lane -> (row r = 16w + 4i + lane/16, physical chunk p = lane%16); it fetches logical chunk p ^ swz(r).
+  // Buffer loads with the LDS modifier: the descriptor ends at the unit's last valid row, so rows past the end
+  // arrive as zeros (their scores are masked anyway) and nothing outside the unit's slab is ever read.  The
+  // loads are issued from inline assembly so that the compiler does not serialise later LDS reads of the
+  // *other* buffer behind them; completion is awaited explicitly (s_waitcnt vmcnt(0)) before the barrier that
+  // publishes the tile.
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kc, 0, len_u * kRowB, 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vc, 0, len_u * kRowB, 0x00020000);
   const int ld_r = lane >> 4;
+  int ld_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    ld_off[i] = (16 * wave + 4 * i + ld_r) * kRowB + (((lane & 15) ^ ((ld_r << 2) | i)) << 4);  // chunk (lane%16)^swz(r)
+  const uint32_t lds_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + wave * 16 * kRowB;
   auto issue_tile = [&](int tile, int buf) {
-    AG_LDS uint8_t *dst = (AG_LDS uint8_t *)smem + buf * 2 * kTileB + wave * 16 * kRowB;
+    const int soff = tile * kTileB;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int r = 16 * wave + 4 * i + ld_r;
-      const int c = (lane & 15) ^ ((ld_r << 2) | i);       // = (lane%16) ^ swz(r)
-      const int grow = min(tile * kBN + r, len_u - 1);     // rows past the end repeat the last valid row (masked)
-      const size_t src = (size_t)grow * D + c * 8;
-      __builtin_amdgcn_global_load_lds(Kc + src, dst + i * 4 * kRowB, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(Vc + src, dst + kTileB + i * 4 * kRowB, 16, 0, 0);
+      const uint32_t dk = lds_base + buf * 2 * kTileB + i * 4 * kRowB;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                   :: "s"(dk), "v"(ld_off[i]), "s"(k_rsrc), "s"(soff) : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                   :: "s"(dk + kTileB), "v"(ld_off[i]), "s"(v_rsrc), "s"(soff) : "memory");
     }
   };
   if (n_tiles > 0) issue_tile(0, 0);
@@ -140,7 +152,10 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   // K fragment (A of S^T): row 32 sub + col, logical chunk 2 ks + hb
   int k_off[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) k_off[ks] = col * kRowB + (((2 * ks + hb) ^ swz(col)) << 4);
+  for (int ks = 0; ks < KS; ++ks) {
+    k_off[ks] = col * kRowB + (((2 * ks + hb) ^ swz(col)) << 4);
+    asm volatile("" : "+v"(k_off[ks]));  // keep the offset in a register instead of recomputing the swizzle per tile
+  }
   // V fragment (A of O^T) by transposing read: 16-lane group gl = lane/16 covers d = 32 dt + 16 (gl%2) + 0..15 and
   // key half hbv = gl/2; lane i = lane%16 supplies the address of row (4 hbv + i/4 [+ 8]), columns 4 (i%4) .. +3
   const int gl = lane >> 4, li = lane & 15;
@@ -153,12 +168,14 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
       const int r = v_row + 8 * h2;
       const int c = 4 * dt + 2 * (gl & 1) + ((li & 3) >> 1);
       v_off[dt][h2] = r * kRowB + ((c ^ swz(r)) << 4) + (li & 1) * 8;
+      asm volatile("" : "+v"(v_off[dt][h2]));
     }
 
   for (int t = 0; t < n_tiles; ++t) {
     const int buf = t & 1;
     const int c0 = t * kBN;
-    __syncthreads();  // tile t has landed (vmcnt drained before the barrier); tile t-1 is fully consumed
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of tile t has landed
+    __syncthreads();                                  // ... and everyone's; tile t-1 is fully consumed
     if (t + 1 < n_tiles) issue_tile(t + 1, buf ^ 1);
     if (c0 >= cnt_wave_hi) continue;  // nothing visible to this wave in the tile (wave-uniform)
     const AG_LDS uint8_t *Kt = (const AG_LDS uint8_t *)smem + buf * 2 * kTileB;
@@ -170,13 +187,18 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc_s[sub][r] = 0.f;
+    bf16x8 ka[KS][2];  // all K fragments of the tile are requested up front; the MFMAs drain them in order
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-        const bf16x8 a = *reinterpret_cast<const AG_LDS bf16x8 *>(Kt + sub * 32 * kRowB + k_off[ks]);
-        acc_s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, qf[ks]), acc_s[sub], 0, 0, 0);
-      }
+      for (int sub = 0; sub < 2; ++sub)
+        ka[ks][sub] = *reinterpret_cast<const AG_LDS bf16x8 *>(Kt + sub * 32 * kRowB + k_off[ks]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+        acc_s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks][sub], __builtin_bit_cast(bf16x8, qf[ks]),
+                                                             acc_s[sub], 0, 0, 0);
     // acc_s[sub][r]: key = c0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col
     if (c0 + kBN > cnt_wave_lo) {  // the tile crosses some query's boundary: mask keys >= cnt_q
 #pragma unroll

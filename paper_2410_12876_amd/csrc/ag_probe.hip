@@ -1,0 +1,96 @@
+// Machine probes used by the benchmark to state what this GPU actually sustains: a dense bf16 MFMA loop with
+// no memory traffic and a streaming copy through HBM.  They put the roofline fractions next to measured peaks
+// as well as the data-sheet ones.  Not part of the attention path.
+#include "ag_internal.h"
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+__global__ __launch_bounds__(256) void ag_probe_mfma_kernel(int iters, float *sink) {
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+    b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; practically never true
+}
+
+__global__ __launch_bounds__(256) void ag_probe_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                            size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+
+extern "C" {
+
+ag_status ag_probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, double *tflops) {
+  if (!ctx || !tflops || iters <= 0) return AG_EINVAL;
+  if (ctx->device < 0) return ag_fail(ctx, AG_EHIP, "context has no device");
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  if (hipSetDevice(ctx->device) != hipSuccess || hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return ag_fail(ctx, AG_EHIP, "ag_probe_mfma: event creation failed");
+  const int blocks = ctx->num_cu * 2;  // 8 waves per CU, 2 per SIMD
+  float *sink = reinterpret_cast<float *>(ctx->d_err) + 8;
+  hipLaunchKernelGGL(ag_probe_mfma_kernel, dim3(blocks), dim3(256), 0, s, iters / 8 + 1, sink);  // warm-up
+  (void)hipEventRecord(e0, s);
+  hipLaunchKernelGGL(ag_probe_mfma_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
+  (void)hipEventRecord(e1, s);
+  float ms = 0.f;
+  hipError_t e = hipEventSynchronize(e1);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return ag_fail(ctx, AG_EHIP, "ag_probe_mfma: %s", hipGetErrorString(e));
+  const double flops = (double)blocks * 4 /*waves*/ * iters * 4 /*mfma*/ * (2.0 * 32 * 32 * 16);
+  *tflops = flops / (ms * 1e-3) / 1e12;
+  return AG_OK;
+}
+
+ag_status ag_probe_copy(ag_ctx *ctx, void *hip_stream, size_t bytes, double *gbs) {
+  if (!ctx || !gbs || bytes < 4096) return AG_EINVAL;
+  if (ctx->device < 0) return ag_fail(ctx, AG_EHIP, "context has no device");
+  bytes &= ~(size_t)255;
+  if (2 * bytes > ctx->ws_bytes) return ag_fail(ctx, AG_EWORKSPACE, "ag_probe_copy: needs a workspace of 2 x %zu bytes", bytes);
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  if (hipSetDevice(ctx->device) != hipSuccess || hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return ag_fail(ctx, AG_EHIP, "ag_probe_copy: event creation failed");
+  const uint4 *src = reinterpret_cast<const uint4 *>(ctx->ws);
+  uint4 *dst = reinterpret_cast<uint4 *>(ctx->ws + bytes);
+  const size_t n = bytes / 16;
+  const int blocks = ctx->num_cu * 8;
+  hipLaunchKernelGGL(ag_probe_copy_kernel, dim3(blocks), dim3(256), 0, s, src, dst, n);  // warm-up
+  (void)hipEventRecord(e0, s);
+  for (int r = 0; r < 4; ++r) hipLaunchKernelGGL(ag_probe_copy_kernel, dim3(blocks), dim3(256), 0, s, src, dst, n);
+  (void)hipEventRecord(e1, s);
+  float ms = 0.f;
+  hipError_t e = hipEventSynchronize(e1);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return ag_fail(ctx, AG_EHIP, "ag_probe_copy: %s", hipGetErrorString(e));
+  *gbs = 4.0 * 2.0 * (double)bytes / (ms * 1e-3) / 1e9;  // read + write
+  return AG_OK;
+}
+
+}  // extern "C"
