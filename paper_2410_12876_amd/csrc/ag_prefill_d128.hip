@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   constexpr int BM = 32 * QW;  // queries per workgroup
   constexpr int KS = D / 16;   // k-steps of S^T
   constexpr int DT = D / 32;   // 32-row tiles of O^T
-  __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * 2 * kTileB];  // [buffer][K|V][row][256 B]
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * 2 * kTileB];  // [K0][K1][V0][V1], each [row][256 B]
 
   const int G = Hq / Hkv;
   const int HB = G / GB;
@@ -103,18 +103,26 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   for (int i = 0; i < 4; ++i)
     ld_off[i] = (16 * wave + 4 * i + ld_r) * kRowB + (((lane & 15) ^ ((ld_r << 2) | i)) << 4);  // chunk (lane%16)^swz(r)
   const uint32_t lds_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + wave * 16 * kRowB;
-  auto issue_tile = [&](int tile, int buf) {
+  auto issue_k = [&](int tile) {
     const int soff = tile * kTileB;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t dk = lds_base + buf * 2 * kTileB + i * 4 * kRowB;
+      const uint32_t dk = lds_base + (tile & 1) * kTileB + i * 4 * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                    :: "s"(dk), "v"(ld_off[i]), "s"(k_rsrc), "s"(soff) : "memory");
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                   :: "s"(dk + kTileB), "v"(ld_off[i]), "s"(v_rsrc), "s"(soff) : "memory");
     }
   };
-  if (n_tiles > 0) issue_tile(0, 0);
+  auto issue_v = [&](int tile) {
+    const int soff = tile * kTileB;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t dv = lds_base + 2 * kTileB + (tile & 1) * kTileB + i * 4 * kRowB;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                   :: "s"(dv), "v"(ld_off[i]), "s"(v_rsrc), "s"(soff) : "memory");
+    }
+  };
+  if (n_tiles > 0) { issue_k(0); issue_v(0); }
+  if (n_tiles > 1) issue_k(1);
 
   // ---- Q fragments (B operand of S^T): lane (query col, half hb), k-step ks: Q[j][16 ks + 8 hb .. +8) ----
   uint4 qf[KS];
@@ -171,23 +179,16 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
       asm volatile("" : "+v"(v_off[dt][h2]));
     }
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    const int c0 = t * kBN;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of tile t has landed
-    __syncthreads();                                  // ... and everyone's; tile t-1 is fully consumed
-    if (t + 1 < n_tiles) issue_tile(t + 1, buf ^ 1);
-    if (c0 >= cnt_wave_hi) continue;  // nothing visible to this wave in the tile (wave-uniform)
-    const AG_LDS uint8_t *Kt = (const AG_LDS uint8_t *)smem + buf * 2 * kTileB;
-    const AG_LDS uint8_t *Vt = Kt + kTileB;
-
-    // ---- S^T = K_tile . Q^T ----
-    f32x16 acc_s[2];
+  // ---- software pipeline: S^T of tile t+1 is issued while the softmax of tile t runs ----
+  // K runs one tile ahead of V.  At the top of step t (after the barrier) K(t+1) and V(t) are resident; the
+  // step then requests K(t+2) into the K buffer that tile t used and V(t+1) into the V buffer of tile t-1.
+  auto s_tile = [&](int tile, f32x16 (&acc)[2]) {  // acc = K(tile) . Q^T
+    const AG_LDS uint8_t *Kt = (const AG_LDS uint8_t *)smem + (tile & 1) * kTileB;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc_s[sub][r] = 0.f;
-    bf16x8 ka[KS][2];  // all K fragments of the tile are requested up front; the MFMAs drain them in order
+      for (int r = 0; r < 16; ++r) acc[sub][r] = 0.f;
+    bf16x8 ka[KS][2];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -197,44 +198,33 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
-        acc_s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks][sub], __builtin_bit_cast(bf16x8, qf[ks]),
-                                                             acc_s[sub], 0, 0, 0);
-    // acc_s[sub][r]: key = c0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col
-    if (c0 + kBN > cnt_wave_lo) {  // the tile crosses some query's boundary: mask keys >= cnt_q
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = c0 + 32 * sub + 8 * (r >> 2) + 4 * hb + (r & 3);
-          if (key >= cnt_q) acc_s[sub][r] = -INFINITY;
-        }
-    }
+        acc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks][sub], __builtin_bit_cast(bf16x8, qf[ks]), acc[sub], 0, 0, 0);
+  };
+  uint4 pf[2][2];  // P fragments (B operand of O^T), [sub][16-key slab]
+  float alpha_pending = 1.f;
+  bool any_raise = false;
+  // softmax of one tile held in acc (key = c0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col) -> pf, l_run, m_run
+  auto softmax_tile = [&](int c0, f32x16 (&acc)[2]) {
     float mx = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[sub][r]);
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[sub][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * qscale;
+    // The reference maximum is raised only when a row exceeds it by more than 2^kRescaleGap; each lane uses
+    // its own factor (1 when it has no need), so a query never depends on the queries sharing its wave.
     const bool raise = mx > m_run + kRescaleGap;
-    if (__any(raise)) {  // rare, wave-uniform branch; each lane rescales by its own factor (1 if it has no need),
-                         // so a query's result never depends on the other queries that share its wave
-      const float m_new = raise ? mx : m_run;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
-    }
+    const float m_new = raise ? mx : m_run;
+    alpha_pending = __builtin_amdgcn_exp2f(m_run - m_new);
+    any_raise = __any(raise);
+    m_run = m_new;
     float psum = 0.f;
-    uint4 pf[2][2];  // P fragments (B operand of O^T), [sub][16-key slab]
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       float p[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(fmaf(acc_s[sub][r], qscale, -m_run));
+        p[r] = __builtin_amdgcn_exp2f(fmaf(acc[sub][r], qscale, -m_run));
         psum += p[r];
       }
 #pragma unroll
@@ -242,9 +232,27 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
         pf[sub][sl] = make_uint4(pack2(p[8 * sl + 0], p[8 * sl + 1]), pack2(p[8 * sl + 2], p[8 * sl + 3]),
                                  pack2(p[8 * sl + 4], p[8 * sl + 5]), pack2(p[8 * sl + 6], p[8 * sl + 7]));
     }
-    l_run += psum;
-
-    // ---- O^T += V^T . P^T ----
+    l_run = l_run * alpha_pending + psum;
+  };
+  auto mask_tile = [&](int c0, f32x16 (&acc)[2]) {
+    if (c0 + kBN > cnt_wave_lo) {  // the tile crosses some query's boundary: mask keys >= cnt_q
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = c0 + 32 * sub + 8 * (r >> 2) + 4 * hb + (r & 3);
+          if (key >= cnt_q) acc[sub][r] = -INFINITY;
+        }
+    }
+  };
+  auto pv_tile = [&](int tile) {  // O^T += V(tile)^T . P^T, after the pending rescale
+    if (any_raise) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha_pending;
+    }
+    const AG_LDS uint8_t *Vt = (const AG_LDS uint8_t *)smem + 2 * kTileB + (tile & 1) * kTileB;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -257,6 +265,49 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
           const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pf[sub][sl]), acc_o[dt], 0, 0, 0);
         }
+    // V fragment reads run four MFMAs ahead of their use
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+      if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+    }
+  };
+  // one pipeline step: cur holds S^T of tile t; nxt receives S^T of tile t+1
+  auto step = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of K(t+1), V(t) has landed
+    __syncthreads();                                  // ... and everyone's; step t-1 is fully consumed
+    if (t + 2 < n_tiles) issue_k(t + 2);
+    if (t + 1 < n_tiles) issue_v(t + 1);
+    const int c0 = t * kBN;
+    const bool vis_cur = c0 < cnt_wave_hi;                                  // wave-uniform
+    const bool vis_nxt = t + 1 < n_tiles && c0 + kBN < cnt_wave_hi;         // wave-uniform
+    if (vis_cur) mask_tile(c0, cur);
+    if (vis_nxt) {
+      s_tile(t + 1, nxt);      // MFMA stream ...
+      softmax_tile(c0, cur);   // ... and an independent VALU stream; the groups below interleave them:
+      // 4 K-fragment reads ahead, then per MFMA one more read and a slice of the softmax arithmetic
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
+      }
+    } else if (vis_cur) {
+      softmax_tile(c0, cur);
+    }
+    if (vis_cur) pv_tile(t);
+  };
+  f32x16 acc_a[2], acc_b[2];
+  if (n_tiles > 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (cnt_wave_hi > 0) s_tile(0, acc_a);
+  }
+  for (int t = 0; t < n_tiles; t += 2) {
+    step(t, acc_a, acc_b);
+    if (t + 1 < n_tiles) step(t + 1, acc_b, acc_a);
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
