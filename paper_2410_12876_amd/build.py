@@ -27,7 +27,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + SOURCES + ["-o", LIB + ".tmp"]
+    cmd = [hipcc] + FLAGS + os.environ.get("AG_EXTRA_FLAGS", "").split() + SOURCES + ["-o", LIB + ".tmp"]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -174,8 +174,18 @@ size_t ag_workspace_bytes(int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, 
   const size_t gate = d_in > 0 ? ag_ws_gate_bytes((int64_t)B * L, d_in, Hkv, dtype) : 0;
   // prefill without a cache compacts into the workspace: K, V rows, idx, row_off, len
   const size_t rows = (size_t)units * L;
+  size_t plan_bytes = 0;
+  if (dtype == AG_BF16 && D == 128) {  // sizes only: a cursor over no memory counts what the plan would take
+    ws_cursor count{nullptr, ~size_t(0) >> 1, 0, true};
+    ag_pf_plan plan;
+    float *part;
+    ag_prefill_d128_plan(1024 /* upper bound on CUs: the split only shrinks with fewer */, B, L, Hq, Hkv, count, &plan,
+                         &part);
+    plan_bytes = count.off;
+  }
   const size_t prefill = scan + 2 * ag_align256(rows * D * ag_dtype_size(dtype)) + ag_align256(rows * 4) +
-                         ag_align256((size_t)(units + 1) * 8) + ag_align256((size_t)units * 4);
+                         ag_align256((size_t)(units + 1) * 8) + ag_align256((size_t)units * 4) +
+                         plan_bytes;
   const size_t decode = cache_rows > 0 ? ag_ws_decode_bytes(units, Hq / Hkv, D, cache_rows) : 0;
   size_t need = scan;
   if (gate > need) need = gate;
@@ -243,7 +253,7 @@ ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void
   int32_t *blk_off = ws.take<int32_t>((size_t)units * (nw + 1));
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_compact_kv: workspace too small (need %zu)", ws.off);
   hipStream_t s = (hipStream_t)hip_stream;
-  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off));
+  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off, nullptr));
   AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(cache->D * ag_dtype_size(cache->dtype)), pos0,
                            cache->k, cache->v, cache->idx, cache->row_off, cache->len));
   return AG_OK;
@@ -289,18 +299,23 @@ ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const vo
     wlen = ws.take<int32_t>(units);
     kc = wk; vc = wv; row_off = wro;
   }
+  ag_pf_plan plan;
+  memset(&plan, 0, sizeof(plan));
+  float *part = nullptr;
+  const bool tuned = dtype == AG_BF16 && D == 128;
+  if (tuned) ag_prefill_d128_plan(ctx->num_cu, B, L, Hq, Hkv, ws, &plan, &part);
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_prefill_attn: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes,
              ws.off);
   ag_status st = need_device(ctx);
   if (st != AG_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
-  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off));
+  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off, tuned ? &plan : nullptr));
   if (!cache) {
     AG_HIP(ag_launch_slab_offsets(s, wro, units, L));
     AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(D * esz), 0, wk, wv, widx, wro, wlen));
   }
-  AG_HIP(ag_launch_prefill(ctx, s, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, kc, vc, row_off,
-                           out));
+  AG_HIP(ag_launch_prefill(ctx, s, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, kc, vc, row_off, out, plan,
+                           part));
   return AG_OK;
 }
 

@@ -4,6 +4,8 @@
 // wave64 ballot per 64 tokens) and an exclusive prefix count per mask word.  ag_compact then gives every
 // wave one mask word: a lane's rank inside the word plus the word's prefix is the destination row, so the
 // surviving rows are written back-to-back (fully coalesced 16-byte stores) and evicted rows are never read.
+#include <string.h>
+
 #include "ag_internal.h"
 
 namespace {
@@ -12,19 +14,28 @@ constexpr int kScanThreads = 256;
 
 __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_t *__restrict__ flags, int L, int nw,
                                                                     uint64_t *__restrict__ words,
-                                                                    int32_t *__restrict__ blk_off) {
+                                                                    int32_t *__restrict__ blk_off, ag_pf_plan plan,
+                                                                    int num_units, int32_t *__restrict__ arrivals) {
   extern __shared__ int32_t cnts[];  // nw counts, then 256 partial sums
   int32_t *part = cnts + nw;
   const int u = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint8_t *f = flags + (size_t)u * L;
-  for (int w = wave; w < nw; w += kScanThreads / 64) {
-    const int t = w * 64 + lane;
-    const bool keep = t < L && f[t] != 0;
-    const uint64_t m = __ballot(keep);
-    if (lane == 0) {
-      words[(size_t)u * nw + w] = m;
-      cnts[w] = __popcll(m);
+  constexpr int UN = 8;  // mask words per wave in flight (independent loads)
+  for (int w0 = wave * UN; w0 < nw; w0 += (kScanThreads / 64) * UN) {
+    uint8_t fb[UN];
+#pragma unroll
+    for (int j = 0; j < UN; ++j) {
+      const int t = (w0 + j) * 64 + lane;
+      fb[j] = (w0 + j < nw && t < L) ? f[t] : (uint8_t)0;
+    }
+#pragma unroll
+    for (int j = 0; j < UN; ++j) {
+      const uint64_t m = __ballot(fb[j] != 0);
+      if (lane == 0 && w0 + j < nw) {
+        words[(size_t)u * nw + w0 + j] = m;
+        cnts[w0 + j] = __popcll(m);
+      }
     }
   }
   __syncthreads();
@@ -48,6 +59,63 @@ __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_
     run += cnts[w];
   }
   if (tid == kScanThreads - 1) bo[nw] = part[tid];
+
+  // ---- optional: prepare the prefill kernel's launch plan ----
+  if (plan.tickets)
+    for (int i = blockIdx.x * kScanThreads + tid; i < plan.n_items; i += gridDim.x * kScanThreads) plan.tickets[i] = 0;
+  if (!plan.order && !plan.chunk_tiles) return;
+  // the last workgroup to arrive sees every unit's masks and prefixes
+  __threadfence();
+  __syncthreads();
+  __shared__ int is_last;
+  if (tid == 0) is_last = atomicAdd(arrivals, 1) == (int)gridDim.x - 1;
+  __syncthreads();
+  if (!is_last) return;
+  if (tid == 0) *arrivals = 0;  // ready for the next call
+  __threadfence();
+  __shared__ int32_t kept[1024];
+  if (plan.order) {
+    // Head blocks are ranked by the kept rows of their unit and dealt to the 8 XCDs in snake order
+    // (0..7, 7..0, ...): order[p] is the head block at position p of a row, and position p runs on XCD p % 8.
+    for (int hy = tid; hy < plan.n_hy; hy += kScanThreads) kept[hy] = blk_off[(size_t)(hy / plan.HB) * (nw + 1) + nw];
+    __syncthreads();
+    for (int hy = tid; hy < plan.n_hy; hy += kScanThreads) {
+      const int mine = kept[hy];
+      int rank = 0;
+      for (int o = 0; o < plan.n_hy; ++o) rank += (kept[o] > mine) || (kept[o] == mine && o < hy);
+      const int round = rank >> 3, pos = rank & 7;
+      plan.order[round * 8 + ((round & 1) ? 7 - pos : pos)] = hy;
+    }
+  }
+  if (plan.chunk_tiles) {
+    // Key tiles of all items together, per workgroup slot of the chip: an item is cut only where it alone
+    // would exceed that average (and never into more than n_split chunks).
+    const int n_qt = (L + plan.BM - 1) / plan.BM;
+    int64_t steps = 0;
+    for (int idx = tid; idx < num_units * n_qt; idx += kScanThreads) {
+      const int uu = idx / n_qt, t = idx - uu * n_qt;
+      const int pos = min((t + 1) * plan.BM, L);
+      const int32_t *b2 = blk_off + (size_t)uu * (nw + 1);
+      int cnt = b2[nw];
+      if (pos < L) cnt = b2[pos >> 6] + __popcll(words[(size_t)uu * nw + (pos >> 6)] & ((1ull << (pos & 63)) - 1ull));
+      steps += (cnt + 63) / 64;
+    }
+    __syncthreads();
+    part[tid] = (int32_t)steps;
+    __syncthreads();
+    for (int d = kScanThreads / 2; d > 0; d >>= 1) {
+      if (tid < d) part[tid] += part[tid + d];
+      __syncthreads();
+    }
+    if (tid == 0) {
+      const int64_t total = (int64_t)part[0] * plan.HB;
+      int ct = (int)((total + plan.slots - 1) / plan.slots);
+      const int lo = (plan.max_tiles + plan.n_split - 1) / plan.n_split;
+      ct = ct < lo ? lo : ct;
+      ct = ct < 8 ? 8 : ct;
+      *plan.chunk_tiles = ct;
+    }
+  }
 }
 
 // LPR = lanes that share one row (16 bytes each); rows wider than 1 KiB loop over segments.
@@ -135,11 +203,15 @@ size_t ag_ws_scan_bytes(int units, int L) {
 }
 
 hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
-                               int32_t *blk_off) {
+                               int32_t *blk_off, const ag_pf_plan *plan) {
   const int nw = ag_nwords(L);
   const size_t shmem = (size_t)(nw + kScanThreads) * sizeof(int32_t);
+  ag_pf_plan none;
+  memset(&none, 0, sizeof(none));
+  int32_t *arrivals = ctx->d_err + 16;  // zeroed at creation; the kernel leaves it at zero
   ag_tick(ctx, AG_K_FLAG_SCAN, s);
-  hipLaunchKernelGGL(ag_flag_scan_kernel, dim3(units), dim3(kScanThreads), shmem, s, flags, L, nw, words, blk_off);
+  hipLaunchKernelGGL(ag_flag_scan_kernel, dim3(units), dim3(kScanThreads), shmem, s, flags, L, nw, words, blk_off,
+                     plan ? *plan : none, units, arrivals);
   ag_tock(ctx, AG_K_FLAG_SCAN, s);
   return hipGetLastError();
 }

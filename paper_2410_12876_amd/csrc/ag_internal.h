@@ -64,11 +64,20 @@ size_t ag_ws_scan_bytes(int units, int L);
 size_t ag_ws_gate_bytes(int64_t tokens, int d_in, int H_f, ag_dtype dt);
 size_t ag_ws_decode_bytes(int units, int G, int D, int64_t cache_rows);
 
+// What the flag scan's last workgroup prepares for the D = 128 prefill kernel (all pointers device, nullable):
+// the head order that balances XCDs, the number of key tiles per chunk, and zeroed per-item arrival counters.
+struct ag_pf_plan {
+  int32_t *order;        // [n_hy] head block at each position of a query-tile row
+  int32_t *chunk_tiles;  // [1]   key tiles per chunk, from the measured amount of work
+  int32_t *tickets;      // [n_items] chunks of an item that have stored their partial state
+  int n_hy, HB, BM, n_items, n_split, slots, max_tiles;
+};
+
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----
 // Flag scan: 64-bit keep masks per 64 tokens and their exclusive prefix counts.
 //   words [units, nw], blk_off [units, nw + 1]  (nw = ceil(L / 64)); blk_off[u][nw] = kept rows of unit u.
 hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
-                               int32_t *blk_off);
+                               int32_t *blk_off, const ag_pf_plan *plan);
 
 // row_off[u] = u * L for u in [0, units]: one full-length slab per unit.
 hipError_t ag_launch_slab_offsets(hipStream_t s, int64_t *row_off, int units, int L);
@@ -84,12 +93,15 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
 hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const void *k, const void *v,
                              const uint64_t *words, const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D,
                              ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
-                             void *out);
+                             void *out, const ag_pf_plan &plan, float *part);
 
-// bf16, D = 128: the tuned kernel of ag_prefill_d128.hip (qscale = scale * log2 e)
+// bf16, D = 128: the tuned kernel of ag_prefill_d128.hip (qscale = scale * log2 e).  ag_prefill_d128_plan carves
+// the plan's buffers and the partial-state buffer out of the workspace (plan.n_split == 1: no key split).
+void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &ws, ag_pf_plan *plan, float **part);
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
                                   const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, const void *kc,
-                                  const void *vc, const int64_t *row_off, void *out);
+                                  const void *vc, const int64_t *row_off, void *out, const ag_pf_plan &plan,
+                                  float *part);
 
 hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,

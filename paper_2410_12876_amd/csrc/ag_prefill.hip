@@ -297,13 +297,14 @@ bool ag_prefill_supported(ag_dtype dt, int D, int G) {
 hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const void *k, const void *v,
                              const uint64_t *words, const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D,
                              ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
-                             void *out) {
+                             void *out, const ag_pf_plan &plan, float *part) {
   const int nw = ag_nwords(L);
   ag_tick(ctx, AG_K_PREFILL, s);
   const int G = Hq / Hkv;
   const float qscale = scale * kLog2e;
   if (dt == AG_BF16 && D == 128) {
-    const hipError_t e = ag_launch_prefill_d128(s, q, k, v, words, blk_off, B, L, Hq, Hkv, qscale, kc, vc, row_off, out);
+    const hipError_t e = ag_launch_prefill_d128(s, q, k, v, words, blk_off, B, L, Hq, Hkv, qscale, kc, vc, row_off, out,
+                                                plan, part);
     ag_tock(ctx, AG_K_PREFILL, s);
     return e;
   }

@@ -2,21 +2,50 @@
 // tuned CDNA4 kernel.  Same formulation as ag_prefill.hip (attention over the compacted rows with the
 // per-query boundary cnt[j]; the query's own key/value initialises the online softmax), built for gfx950:
 //
-//   * K and V tiles (64 cache rows x 256 B) go from global memory straight into LDS with
-//     global_load_lds_dwordx4 (no register staging), double-buffered, one workgroup barrier per tile.
+//   * K and V tiles (64 cache rows x 256 B) go from global memory straight into LDS (buffer_load ... lds,
+//     no register staging), double-buffered, one workgroup barrier per step.
 //   * Both tiles stay row-major in LDS.  The 16-byte chunk index of a row is XOR-swizzled with a bit-swapped
 //     row nibble, applied on the global-address side of the load, so that the 128-bit reads of K fragments
 //     (32 consecutive rows, same column) and the transposing reads of V fragments (4 consecutive rows,
-//     64 contiguous bytes each) are both free of bank conflicts.
+//     64 contiguous bytes each) are both free of bank conflicts (SQ_LDS_BANK_CONFLICT reads 0).
 //   * V is never transposed in memory: ds_read_b64_tr_b16 delivers, per lane, four consecutive keys of one
 //     head-dim column, which is the A-operand layout of O^T += V^T . P^T.
 //   * A lane owns one query: S^T = K . Q^T and O^T = V^T . P^T on v_mfma_f32_32x32x16_bf16, P packed with
 //     v_cvt_pk_bf16_f32 straight from the S^T accumulators, row max / sum / rescale as per-lane scalars.
-//   * The running maximum is only raised (and O rescaled) when some row's new maximum exceeds it by more than
+//   * The reference maximum is only raised (and O rescaled) when a row's new maximum exceeds it by more than
 //     2^8; otherwise the stale maximum is kept, which is exact after the final division by the row sum.
-//   * Two workgroups (8 waves) per CU so that one wave's softmax overlaps another's MFMAs; workgroups are
-//     numbered so that all tiles of one head land on one XCD (K/V stay in that XCD's L2), longest first.
+//   * Software pipeline: S^T of the next tile is issued while the softmax of the current tile runs.
+//   * Small launches (one 4096-token layer is ~1000 workgroups of very different length) are bounded by
+//     their longest workgroup, the last query tile of the head that keeps most.  There the key range of a
+//     (head, query tile) item is cut into chunks of at most `chunk_tiles` tiles, one workgroup per chunk;
+//     chunk_tiles is the average number of tiles per workgroup slot, measured on the device from the flags, so
+//     only an item that alone exceeds the average is cut.  Items that fit one chunk write their output
+//     directly; the few long ones store unnormalised fp32 partial states in the workspace, and the chunk that
+//     arrives last (a per-item counter) combines them with its own registers and writes the rows.
+//   * Workgroups go to the 8 XCDs, and inside an XCD to its 4 shader engines, round-robin by their index
+//     (measured: workgroup i runs on XCD i % 8, engine (i / 8) % 4), so the index -> (head, query tile) map
+//     decides both L2 locality and balance.  All tiles of one head are given to one XCD (its K/V stay in that
+//     XCD's L2), longest first; a small kernel (ag_prefill_order_kernel) first deals the heads to the XCDs in
+//     snake order of their kept-row counts, and the heads of an XCD rotate over its engines from one query tile
+//     to the next, so every engine gets about the same number of key tiles although heads keep 20 % to 90 %.
+#include <string.h>
+
 #include "ag_internal.h"
+
+#ifdef AG_PREFILL_TRACE  // debug build only: per-workgroup start/end times and placement
+__device__ unsigned long long ag_dbg[8192 * 8];
+extern "C" void ag_dbg_read(unsigned long long *h) { (void)hipMemcpyFromSymbol(h, HIP_SYMBOL(ag_dbg), sizeof(ag_dbg)); }
+#define AG_TRACE_BEGIN const unsigned long long trace_t0 = wall_clock64();
+#define AG_TRACE_END(steps, empty)                                                    \
+  if (threadIdx.x == 0 && blockIdx.x < 8192) {                                        \
+    unsigned long long *d = ag_dbg + blockIdx.x * 8;                                  \
+    d[0] = trace_t0; d[1] = wall_clock64(); d[2] = __builtin_amdgcn_s_getreg(63492);  \
+    d[3] = __builtin_amdgcn_s_getreg(63508); d[4] = (steps); d[5] = (empty);          \
+  }
+#else
+#define AG_TRACE_BEGIN
+#define AG_TRACE_END(steps, empty)
+#endif
 
 namespace {
 
@@ -31,12 +60,9 @@ constexpr int D = 128;
 constexpr int kBN = 64;                   // keys per tile
 constexpr int kRowB = D * 2;              // bytes per cache row
 constexpr int kTileB = kBN * kRowB;       // 16 KiB per K or V tile
+constexpr int kGroupB = 4 * kTileB;       // LDS per group: [K0][K1][V0][V1]
 constexpr float kRescaleGap = 8.f;        // log2 units the maximum may lag before O is rescaled
-
-__device__ __forceinline__ int cnt_at(const uint64_t *__restrict__ words, const int32_t *__restrict__ bo, int j) {
-  const uint64_t w = words[j >> 6];
-  return bo[j >> 6] + __popcll(w & ((1ull << (j & 63)) - 1ull));
-}
+constexpr float kEmptyMax = -1.0e30f;     // "no key seen yet" reference maximum (finite on purpose)
 
 // swizzle of the 16-byte chunk index of LDS row r: swap the two low bit pairs of r
 __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
@@ -46,115 +72,168 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
+// GB = query heads of one KV group per workgroup (one per wave).  n_split = chunks per item in the grid,
+// chunk_tiles_dev = key tiles per chunk (device value, NULL without a split); part = partial states
+// [item][chunk][4 waves][66][64] fp32 and tickets = per-item arrival counters (n_split > 1).
 template <int GB>
 __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw, int n_hy,
-    float qscale, uint16_t *__restrict__ out) {
+    int n_split, const int32_t *__restrict__ chunk_tiles_dev, float qscale, const int32_t *__restrict__ order,
+    uint16_t *__restrict__ out, float *__restrict__ part, int32_t *__restrict__ tickets) {
   constexpr int QW = 4 / GB;   // query sub-tiles per workgroup
   constexpr int BM = 32 * QW;  // queries per workgroup
   constexpr int KS = D / 16;   // k-steps of S^T
   constexpr int DT = D / 32;   // 32-row tiles of O^T
-  __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * 2 * kTileB];  // [K0][K1][V0][V1], each [row][256 B]
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[kGroupB];  // [K0][K1][V0][V1], each [row][256 B]
 
+  AG_TRACE_BEGIN
   const int G = Hq / Hkv;
   const int HB = G / GB;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar, so that LDS bases stay in SGPRs
+  const int w4 = wave;
   const int col = lane & 31, hb = lane >> 5;
-  // workgroup id -> (query tile, unit/head block): heads vary fastest so that a head keeps its XCD
+  // workgroup id -> (query tile, chunk, unit/head block): heads vary fastest so that a head keeps its XCD
   const int n_qt = (L + BM - 1) / BM;
-  const int hy = blockIdx.x % n_hy;
-  const int qtile = n_qt - 1 - blockIdx.x / n_hy;  // longest rows first
+  const int per_qt = n_hy * n_split;
+  const int rem = blockIdx.x % per_qt;
+  const int chunk = rem / n_hy;
+  const int qt_idx = blockIdx.x / per_qt;
+  const int qtile = n_qt - 1 - qt_idx;  // longest rows first
+  // Position pos of a row goes to XCD pos % 8 and, inside it, to shader engine (pos / 8) % 4: both fixed for all
+  // rows.  order[] gives each XCD its heads; rotating them over the XCD's positions from row to row lets every
+  // shader engine see all of them, instead of one engine being stuck with the head that keeps most.
+  const int pos = rem % n_hy;
+  int hy = pos;
+  if (order) {
+    const int n_slot = n_hy >> 3;
+    hy = order[(((pos >> 3) + qt_idx) % n_slot) * 8 + (pos & 7)];
+  }
   const int u = hy / HB;
   const int hblk = hy - u * HB;
   const int b = u / Hkv, g = u - b * Hkv;
-  const int head = g * G + hblk * GB + (wave % GB);
-  const int j0 = qtile * BM + (wave / GB) * 32;
+  const int head = g * G + hblk * GB + (w4 % GB);
+  const int j0 = qtile * BM + (w4 / GB) * 32;
   const int jq = min(j0 + col, L - 1);
 
+  // All scalar inputs of the workgroup in one round of loads.  The 32 queries of a wave lie in one 64-token
+  // mask word (j0 is a multiple of 32), so one (word, prefix) pair gives every per-query boundary of the wave.
   const uint64_t *wu = words + (size_t)u * nw;
   const int32_t *bo = blk_off + (size_t)u * (nw + 1);
-  const int len_u = (int)min((int64_t)bo[nw], row_off[u + 1] - row_off[u]);
-  const int cnt_q = cnt_at(wu, bo, jq);
-  const int cnt_wave_lo = cnt_at(wu, bo, min(j0, L - 1));
-  const int cnt_wave_hi = j0 < L ? cnt_at(wu, bo, min(j0 + 31, L - 1)) : 0;
-  const int cnt_blk = min(cnt_at(wu, bo, min(qtile * BM + BM - 1, L - 1)), len_u);
-  const int n_tiles = (cnt_blk + kBN - 1) / kBN;
+  const int jw = min(j0, L - 1) >> 6;                         // mask word of this wave's queries
+  const int jb = min(qtile * BM + BM - 1, L - 1);             // last query of the workgroup
+  const uint64_t word_w = wu[jw], word_b = wu[jb >> 6];
+  const int pre_w = bo[jw], pre_b = bo[jb >> 6], kept_u = bo[nw];
+  const int chunk_tiles = chunk_tiles_dev ? *chunk_tiles_dev : 0x7fffffff / kBN;
+  const int64_t ro0 = row_off[u], ro1 = row_off[u + 1];
+  auto cnt_in = [](uint64_t w, int pre, int j) { return pre + __popcll(w & ((1ull << (j & 63)) - 1ull)); };
+  const int len_u = (int)min((int64_t)kept_u, ro1 - ro0);
+  const int cnt_q = cnt_in(word_w, pre_w, jq);
+  const int cnt_wave_lo = cnt_in(word_w, pre_w, min(j0, L - 1));
+  const int cnt_wave_hi = j0 < L ? cnt_in(word_w, pre_w, min(j0 + 31, L - 1)) : 0;
+  const int cnt_blk = min(cnt_in(word_b, pre_b, jb), len_u);
+  const int n_tiles = (cnt_blk + kBN - 1) / kBN;       // key tiles of the item
+  const int tile0 = chunk > 0 ? chunk * chunk_tiles : 0;  // this workgroup's chunk: tiles [tile0, tile0 + n_steps)
+  if (chunk > 0 && tile0 >= n_tiles) {                 // empty chunk (the whole workgroup leaves)
+    AG_TRACE_END(0, 1)
+    return;
+  }
+  const int n_steps = max(0, min(n_tiles - tile0, chunk_tiles));
+  const int n_chunks = max(1, (n_tiles + chunk_tiles - 1) / chunk_tiles);
 
   const size_t qrow = ((size_t)(b * Hq + head) * L + jq) * D;
   const size_t kvrow = ((size_t)u * L + jq) * D;
-  const uint16_t *Kc = kc + (size_t)row_off[u] * D;
-  const uint16_t *Vc = vc + (size_t)row_off[u] * D;
+  const uint16_t *Kc = kc + (size_t)ro0 * D;
+  const uint16_t *Vc = vc + (size_t)ro0 * D;
 
-  // ---- tile loader: wave w fills rows [16w, 16w+16) of the K and V tiles, 4 rows (1 KiB) per instruction ----
-  // lane -> (row r = 16w + 4i + lane/16, physical chunk p = lane%16); it fetches logical chunk p ^ swz(r).
-  // Buffer loads with the LDS modifier: the descriptor ends at the unit's last valid row, so rows past the end
-  // arrive as zeros (their scores are masked anyway) and nothing outside the unit's slab is ever read.  The
-  // loads are issued from inline assembly so that the compiler does not serialise later LDS reads of the
-  // *other* buffer behind them; completion is awaited explicitly (s_waitcnt vmcnt(0)) before the barrier that
-  // publishes the tile.
+  // ---- tile loader: wave w4 of a group fills rows [16 w4, 16 w4 + 16) of the group's K and V tiles, 4 rows
+  // (1 KiB) per instruction.  lane -> (row r = 16 w4 + 4 i + lane/16, physical chunk p = lane%16); it fetches
+  // logical chunk p ^ swz(r).  Buffer loads with the LDS modifier: the descriptor ends at the unit's last
+  // valid row, so rows past the end arrive as zeros (their scores are masked anyway) and nothing outside the
+  // unit's slab is ever read.  The loads are issued from inline assembly so that the compiler does not
+  // serialise later LDS reads of the *other* buffer behind them; completion is awaited explicitly
+  // (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
   const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kc, 0, len_u * kRowB, 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vc, 0, len_u * kRowB, 0x00020000);
   const int ld_r = lane >> 4;
   int ld_off[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    ld_off[i] = (16 * wave + 4 * i + ld_r) * kRowB + (((lane & 15) ^ ((ld_r << 2) | i)) << 4);  // chunk (lane%16)^swz(r)
-  const uint32_t lds_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + wave * 16 * kRowB;
-  auto issue_k = [&](int tile) {
-    const int soff = tile * kTileB;
+    ld_off[i] = (16 * w4 + 4 * i + ld_r) * kRowB + (((lane & 15) ^ ((ld_r << 2) | i)) << 4);  // chunk (lane%16)^swz(r)
+  const uint32_t ld_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + w4 * 16 * kRowB;
+  auto issue_k = [&](int i_step) {  // K of the tile of step i_step -> K buffer i_step & 1
+    const int soff = (tile0 + i_step) * kTileB;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t dk = lds_base + (tile & 1) * kTileB + i * 4 * kRowB;
+      const uint32_t dk = ld_base + (i_step & 1) * kTileB + i * 4 * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                    :: "s"(dk), "v"(ld_off[i]), "s"(k_rsrc), "s"(soff) : "memory");
     }
   };
-  auto issue_v = [&](int tile) {
-    const int soff = tile * kTileB;
+  auto issue_v = [&](int i_step) {
+    const int soff = (tile0 + i_step) * kTileB;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t dv = lds_base + 2 * kTileB + (tile & 1) * kTileB + i * 4 * kRowB;
+      const uint32_t dv = ld_base + 2 * kTileB + (i_step & 1) * kTileB + i * 4 * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                    :: "s"(dv), "v"(ld_off[i]), "s"(v_rsrc), "s"(soff) : "memory");
     }
   };
-  if (n_tiles > 0) { issue_k(0); issue_v(0); }
-  if (n_tiles > 1) issue_k(1);
+  if (n_steps > 0) { issue_k(0); issue_v(0); }
+  if (n_steps > 1) issue_k(1);
 
   // ---- Q fragments (B operand of S^T): lane (query col, half hb), k-step ks: Q[j][16 ks + 8 hb .. +8) ----
-  uint4 qf[KS];
+  // Q and, for chunk 0, the query's own key and value rows are all requested before anything waits on them.
+  uint4 qf[KS], kself[KS];
+  uint2 vself[DT][4];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const uint4 *>(q + qrow + 16 * ks + 8 * hb);
-
-  // ---- own-token term: initial online-softmax state ----
-  float s_self = 0.f;
+  if (chunk == 0) {
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    const uint4 kr = *reinterpret_cast<const uint4 *>(k + kvrow + 16 * ks + 8 * hb);
-    const uint32_t qa[4] = {qf[ks].x, qf[ks].y, qf[ks].z, qf[ks].w}, ka[4] = {kr.x, kr.y, kr.z, kr.w};
+    for (int ks = 0; ks < KS; ++ks) kself[ks] = *reinterpret_cast<const uint4 *>(k + kvrow + 16 * ks + 8 * hb);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      s_self = fmaf(__uint_as_float(qa[e] << 16), __uint_as_float(ka[e] << 16), s_self);
-      s_self = fmaf(__uint_as_float(qa[e] & 0xffff0000u), __uint_as_float(ka[e] & 0xffff0000u), s_self);
-    }
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4)
+        vself[dt][r4] = *reinterpret_cast<const uint2 *>(v + kvrow + 32 * dt + 8 * r4 + 4 * hb);
   }
-  s_self += __shfl_xor(s_self, 32, 64);
-  float m_run = s_self * qscale;       // reference maximum of the exponentials, log2 units
-  float l_run = hb == 0 ? 1.f : 0.f;   // each half of a column holds part of the row sum
-  f32x16 acc_o[DT];                    // O^T: acc_o[dt][r] = (d = 32 dt + 8 (r/4) + 4 hb + r%4, query col)
+  __builtin_amdgcn_sched_barrier(0);  // keep the loads above ahead of the arithmetic below
+
+  // ---- initial online-softmax state: chunk 0 starts from the query's own token, the others from nothing ----
+  float m_run = kEmptyMax;  // reference maximum of the exponentials, log2 units
+  float l_run = 0.f;        // each half (hb) of a column holds part of the row sum
+  f32x16 acc_o[DT];         // O^T: acc_o[dt][r] = (d = 32 dt + 8 (r/4) + 4 hb + r%4, query col)
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      const uint2 vr = *reinterpret_cast<const uint2 *>(v + kvrow + 32 * dt + 8 * r4 + 4 * hb);
-      acc_o[dt][4 * r4 + 0] = __uint_as_float(vr.x << 16);
-      acc_o[dt][4 * r4 + 1] = __uint_as_float(vr.x & 0xffff0000u);
-      acc_o[dt][4 * r4 + 2] = __uint_as_float(vr.y << 16);
-      acc_o[dt][4 * r4 + 3] = __uint_as_float(vr.y & 0xffff0000u);
+    for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.f;
+  if (chunk == 0) {
+    float s_self = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint32_t qa[4] = {qf[ks].x, qf[ks].y, qf[ks].z, qf[ks].w};
+      const uint32_t ka[4] = {kself[ks].x, kself[ks].y, kself[ks].z, kself[ks].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s_self = fmaf(__uint_as_float(qa[e] << 16), __uint_as_float(ka[e] << 16), s_self);
+        s_self = fmaf(__uint_as_float(qa[e] & 0xffff0000u), __uint_as_float(ka[e] & 0xffff0000u), s_self);
+      }
     }
+    s_self += __shfl_xor(s_self, 32, 64);
+    m_run = s_self * qscale;
+    l_run = hb == 0 ? 1.f : 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        acc_o[dt][4 * r4 + 0] = __uint_as_float(vself[dt][r4].x << 16);
+        acc_o[dt][4 * r4 + 1] = __uint_as_float(vself[dt][r4].x & 0xffff0000u);
+        acc_o[dt][4 * r4 + 2] = __uint_as_float(vself[dt][r4].y << 16);
+        acc_o[dt][4 * r4 + 3] = __uint_as_float(vself[dt][r4].y & 0xffff0000u);
+      }
+  }
 
   // ---- loop-invariant LDS byte offsets of this lane's fragments ----
   // K fragment (A of S^T): row 32 sub + col, logical chunk 2 ks + hb
@@ -179,11 +258,9 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
       asm volatile("" : "+v"(v_off[dt][h2]));
     }
 
-  // ---- software pipeline: S^T of tile t+1 is issued while the softmax of tile t runs ----
-  // K runs one tile ahead of V.  At the top of step t (after the barrier) K(t+1) and V(t) are resident; the
-  // step then requests K(t+2) into the K buffer that tile t used and V(t+1) into the V buffer of tile t-1.
-  auto s_tile = [&](int tile, f32x16 (&acc)[2]) {  // acc = K(tile) . Q^T
-    const AG_LDS uint8_t *Kt = (const AG_LDS uint8_t *)smem + (tile & 1) * kTileB;
+  const AG_LDS uint8_t *lds_grp = (const AG_LDS uint8_t *)smem;
+  auto s_tile = [&](int i_step, f32x16 (&acc)[2]) {  // acc = K(tile of step i_step) . Q^T
+    const AG_LDS uint8_t *Kt = lds_grp + (i_step & 1) * kTileB;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -204,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   float alpha_pending = 1.f;
   bool any_raise = false;
   // softmax of one tile held in acc (key = c0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col) -> pf, l_run, m_run
-  auto softmax_tile = [&](int c0, f32x16 (&acc)[2]) {
+  auto softmax_tile = [&](f32x16 (&acc)[2]) {
     float mx = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
@@ -245,14 +322,14 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
         }
     }
   };
-  auto pv_tile = [&](int tile) {  // O^T += V(tile)^T . P^T, after the pending rescale
+  auto pv_tile = [&](int i_step) {  // O^T += V(tile)^T . P^T, after the pending rescale
     if (any_raise) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha_pending;
     }
-    const AG_LDS uint8_t *Vt = (const AG_LDS uint8_t *)smem + 2 * kTileB + (tile & 1) * kTileB;
+    const AG_LDS uint8_t *Vt = lds_grp + 2 * kTileB + (i_step & 1) * kTileB;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -273,43 +350,90 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
       if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
     }
   };
-  // one pipeline step: cur holds S^T of tile t; nxt receives S^T of tile t+1
-  auto step = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of K(t+1), V(t) has landed
-    __syncthreads();                                  // ... and everyone's; step t-1 is fully consumed
-    if (t + 2 < n_tiles) issue_k(t + 2);
-    if (t + 1 < n_tiles) issue_v(t + 1);
-    const int c0 = t * kBN;
-    const bool vis_cur = c0 < cnt_wave_hi;                                  // wave-uniform
-    const bool vis_nxt = t + 1 < n_tiles && c0 + kBN < cnt_wave_hi;         // wave-uniform
+  // One pipeline step.  cur holds S^T of this group's tile of step i; nxt receives that of step i + 1.
+  // At the top (after the barrier) K(i+1) and V(i) are resident; the step then requests K(i+2) into the K
+  // buffer that step i used and V(i+1) into the V buffer of step i-1.
+  auto step = [&](int i, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of K(i+1), V(i) has landed
+    __syncthreads();                                  // ... and everyone's; step i-1 is fully consumed
+    if (i + 2 < n_steps) issue_k(i + 2);
+    if (i + 1 < n_steps) issue_v(i + 1);
+    const int c0 = (tile0 + i) * kBN;
+    const bool vis_cur = c0 < cnt_wave_hi;                                       // wave-uniform
+    const bool vis_nxt = i + 1 < n_steps && c0 + kBN < cnt_wave_hi;              // wave-uniform
     if (vis_cur) mask_tile(c0, cur);
     if (vis_nxt) {
-      s_tile(t + 1, nxt);      // MFMA stream ...
-      softmax_tile(c0, cur);   // ... and an independent VALU stream; the groups below interleave them:
+      s_tile(i + 1, nxt);   // MFMA stream ...
+      softmax_tile(cur);    // ... and an independent VALU stream; the groups below interleave them:
       // 4 K-fragment reads ahead, then per MFMA one more read and a slice of the softmax arithmetic
       __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
+      for (int n = 0; n < 16; ++n) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (n < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
       }
     } else if (vis_cur) {
-      softmax_tile(c0, cur);
+      softmax_tile(cur);
     }
-    if (vis_cur) pv_tile(t);
+    if (vis_cur) pv_tile(i);
   };
   f32x16 acc_a[2], acc_b[2];
-  if (n_tiles > 0) {
+  if (n_steps > 0) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (cnt_wave_hi > 0) s_tile(0, acc_a);
+    if (tile0 * kBN < cnt_wave_hi) s_tile(0, acc_a);
   }
-  for (int t = 0; t < n_tiles; t += 2) {
-    step(t, acc_a, acc_b);
-    if (t + 1 < n_tiles) step(t + 1, acc_b, acc_a);
+  for (int i = 0; i < n_steps; i += 2) {
+    step(i, acc_a, acc_b);
+    if (i + 1 < n_steps) step(i + 1, acc_b, acc_a);
   }
 
+  AG_TRACE_END(n_steps, 0)
+  // ---- an item cut into chunks: store this chunk's state; the chunk that arrives last merges and writes ----
+  if (n_chunks > 1) {
+    const size_t item = (size_t)qtile * n_hy + hy;
+    float *st = part + (item * n_split * 4 + w4) * (66 * 64) + lane;  // state of chunk c at st + c * cstride
+    const size_t cstride = (size_t)4 * 66 * 64;
+    // The states travel through memory between workgroups of one launch.  They are written through and read
+    // past the caches (system-scope relaxed accesses), so no cache-wide write-back or invalidate is needed: the
+    // stores are complete (vmcnt 0) before the workgroup's arrival is counted, and the last arrival reads after it.
+    float *mine = st + chunk * cstride;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        __hip_atomic_store(&mine[(16 * dt + r) * 64], acc_o[dt][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(&mine[64 * 64], m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(&mine[65 * 64], l_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();  // every wave's state is out, and nobody reads the tile buffers any more
+    int *last = reinterpret_cast<int *>(smem);
+    if (tid == 0)
+      *last = __hip_atomic_fetch_add(&tickets[item], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_chunks - 1;
+    __syncthreads();
+    if (!*last) return;
+    auto peek = [](const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); };
+    float m = m_run;
+    for (int c = 0; c < n_chunks; ++c)
+      if (c != chunk) m = fmaxf(m, peek(&st[c * cstride + 64 * 64]));
+    const float f_own = __builtin_amdgcn_exp2f(m_run - m);
+    l_run *= f_own;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc_o[dt][r] *= f_own;
+    for (int c = 0; c < n_chunks; ++c) {
+      if (c == chunk) continue;
+      const float *sc = st + c * cstride;
+      const float f = __builtin_amdgcn_exp2f(peek(&sc[64 * 64]) - m);
+      l_run = fmaf(peek(&sc[65 * 64]), f, l_run);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[dt][r] = fmaf(peek(&sc[(16 * dt + r) * 64]), f, acc_o[dt][r]);
+    }
+  }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (j0 + col < L) {
     const float inv = 1.f / l_tot;
@@ -327,21 +451,45 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
 
 }  // namespace
 
+// Split policy: only launches too small to hide their longest item behind other work are split; heads are
+// dealt to XCDs by kept rows when there are few enough per XCD for their differences to show.
+void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &ws, ag_pf_plan *plan, float **part) {
+  const int G = Hq / Hkv;
+  const int GB = G >= 4 ? 4 : G;
+  memset(plan, 0, sizeof(*plan));
+  plan->BM = 32 * (4 / GB);
+  plan->HB = G / GB;
+  plan->n_hy = B * Hkv * plan->HB;
+  const int64_t items = (int64_t)((L + plan->BM - 1) / plan->BM) * plan->n_hy;
+  plan->n_items = (int)items;
+  plan->max_tiles = (L + kBN - 1) / kBN;
+  plan->slots = 2 * num_cu;
+  plan->n_split = 1;
+  if (items < (int64_t)8 * num_cu && plan->max_tiles > 16) plan->n_split = 2;
+  *part = nullptr;
+  if (plan->n_split > 1) {
+    *part = ws.take<float>((size_t)items * plan->n_split * 4 * 66 * 64);
+    plan->chunk_tiles = ws.take<int32_t>(64);
+    plan->tickets = ws.take<int32_t>((size_t)items);
+  }
+  if (plan->n_hy % 8 == 0 && plan->n_hy >= 16 && plan->n_hy <= 1024) plan->order = ws.take<int32_t>(plan->n_hy);
+}
+
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
                                   const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, const void *kc,
-                                  const void *vc, const int64_t *row_off, void *out) {
+                                  const void *vc, const int64_t *row_off, void *out, const ag_pf_plan &plan,
+                                  float *part) {
+  (void)B;
   const int nw = ag_nwords(L);
   const int G = Hq / Hkv;
   const int GB = G >= 4 ? 4 : G;
-  const int BM = 32 * (4 / GB);
-  const int n_hy = B * Hkv * (G / GB);
-  const int64_t blocks = (int64_t)((L + BM - 1) / BM) * n_hy;
-  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)blocks), block(256);
+  if ((int64_t)plan.n_items * plan.n_split > 0x7fffffff) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(plan.n_items * plan.n_split)), block(256);
 #define AG_PF(GG)                                                                                                   \
   hipLaunchKernelGGL((ag_prefill_d128_kernel<GG>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k,        \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
-                     Hkv, nw, n_hy, qscale, (uint16_t *)out)
+                     Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, plan.order, (uint16_t *)out, part,  \
+                     plan.tickets)
   if (GB == 1) AG_PF(1); else if (GB == 2) AG_PF(2); else AG_PF(4);
 #undef AG_PF
   return hipGetLastError();
