@@ -64,44 +64,49 @@ __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_
   if (plan.tickets)
     for (int i = blockIdx.x * kScanThreads + tid; i < plan.n_items; i += gridDim.x * kScanThreads) plan.tickets[i] = 0;
   if (!plan.order && !plan.chunk_tiles) return;
-  // the last workgroup to arrive sees every unit's masks and prefixes
-  __threadfence();
-  __syncthreads();
+  // The workgroup that arrives last turns the units' kept-row counts into the plan.  The counts cross
+  // workgroups inside one launch, so they are written through and read past the caches (system-scope relaxed
+  // accesses, complete before the arrival is counted) instead of paying for cache-wide fences.
   __shared__ int is_last;
-  if (tid == 0) is_last = atomicAdd(arrivals, 1) == (int)gridDim.x - 1;
+  if (tid == 0) {
+    __hip_atomic_store(&plan.kept[u], part[kScanThreads - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    is_last = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1;
+    if (is_last) __hip_atomic_store(arrivals, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+  }
   __syncthreads();
   if (!is_last) return;
-  if (tid == 0) *arrivals = 0;  // ready for the next call
-  __threadfence();
   __shared__ int32_t kept[1024];
+  for (int i = tid; i < num_units && i < 1024; i += kScanThreads)
+    kept[i] = __hip_atomic_load(&plan.kept[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  __syncthreads();
   if (plan.order) {
     // Head blocks are ranked by the kept rows of their unit and dealt to the 8 XCDs in snake order
     // (0..7, 7..0, ...): order[p] is the head block at position p of a row, and position p runs on XCD p % 8.
-    for (int hy = tid; hy < plan.n_hy; hy += kScanThreads) kept[hy] = blk_off[(size_t)(hy / plan.HB) * (nw + 1) + nw];
-    __syncthreads();
     for (int hy = tid; hy < plan.n_hy; hy += kScanThreads) {
-      const int mine = kept[hy];
+      const int mine = kept[hy / plan.HB];
       int rank = 0;
-      for (int o = 0; o < plan.n_hy; ++o) rank += (kept[o] > mine) || (kept[o] == mine && o < hy);
+      for (int o = 0; o < plan.n_hy; ++o) {
+        const int other = kept[o / plan.HB];
+        rank += (other > mine) || (other == mine && o < hy);
+      }
       const int round = rank >> 3, pos = rank & 7;
       plan.order[round * 8 + ((round & 1) ? 7 - pos : pos)] = hy;
     }
   }
   if (plan.chunk_tiles) {
-    // Key tiles of all items together, per workgroup slot of the chip: an item is cut only where it alone
-    // would exceed that average (and never into more than n_split chunks).
+    // Key tiles of all items together (a unit's kept rows taken as evenly spread over its tokens), per
+    // workgroup slot of the chip: an item is cut only where it alone would exceed that average, and never
+    // into more than n_split chunks.
     const int n_qt = (L + plan.BM - 1) / plan.BM;
-    int64_t steps = 0;
+    int steps = 0;
     for (int idx = tid; idx < num_units * n_qt; idx += kScanThreads) {
       const int uu = idx / n_qt, t = idx - uu * n_qt;
-      const int pos = min((t + 1) * plan.BM, L);
-      const int32_t *b2 = blk_off + (size_t)uu * (nw + 1);
-      int cnt = b2[nw];
-      if (pos < L) cnt = b2[pos >> 6] + __popcll(words[(size_t)uu * nw + (pos >> 6)] & ((1ull << (pos & 63)) - 1ull));
-      steps += (cnt + 63) / 64;
+      const int64_t pos = min((t + 1) * plan.BM, L);
+      steps += (int)(((int64_t)kept[uu] * pos / L + 63) / 64);
     }
     __syncthreads();
-    part[tid] = (int32_t)steps;
+    part[tid] = steps;
     __syncthreads();
     for (int d = kScanThreads / 2; d > 0; d >>= 1) {
       if (tid < d) part[tid] += part[tid + d];

@@ -97,32 +97,43 @@ __global__ __launch_bounds__(256) void ag_gate_f32_kernel(const float *__restric
 }
 
 // Sum the K splits in order, add bias, threshold, write logits [tokens, H_f] and flags [B, H_f, L].
+constexpr int kFinTok = 16;  // tokens per finalize workgroup
+
 __global__ __launch_bounds__(256) void ag_gate_finalize_kernel(const float *__restrict__ partial, int splits,
                                                                int64_t tokens_pad, int64_t tokens, int L, int H_f,
                                                                const float *__restrict__ bias, float thr, int n_sink,
                                                                float *__restrict__ logits,
                                                                uint8_t *__restrict__ flags) {
-  __shared__ uint8_t fl[kNP][64];
-  const int64_t tok0 = (int64_t)blockIdx.x * 64;
-  for (int e = threadIdx.x; e < 64 * H_f; e += 256) {
-    const int tl = e / H_f, h = e - tl * H_f;
-    const int64_t tok = tok0 + tl;
-    if (tok >= tokens) continue;
-    float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) s += partial[((size_t)sp * tokens_pad + tok) * kNP + h];
-    s += bias[h];
-    if (logits) logits[(size_t)tok * H_f + h] = s;
-    const int t = (int)(tok % L);
-    fl[h][tl] = (s > thr || t < n_sink) ? 1 : 0;
+  __shared__ uint8_t fl[kNP][kFinTok];
+  const int64_t tok0 = (int64_t)blockIdx.x * kFinTok;
+  const int h = threadIdx.x & 31;
+  // thread -> (token tok0 + tid/32 [+ 8], head h): the K splits of both elements are fetched as independent loads
+  float s[2] = {0.f, 0.f};
+  int64_t tok[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) tok[i] = min(tok0 + (threadIdx.x >> 5) + 8 * i, tokens - 1);
+#pragma unroll 4
+  for (int sp = 0; sp < splits; ++sp)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) s[i] += partial[((size_t)sp * tokens_pad + tok[i]) * kNP + h];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int tl = (threadIdx.x >> 5) + 8 * i;
+    if (h < H_f && tok0 + tl < tokens) {
+      const float v = s[i] + bias[h];
+      if (logits) logits[(size_t)tok[i] * H_f + h] = v;
+      const int t = (int)(tok[i] % L);
+      fl[h][tl] = (v > thr || t < n_sink) ? 1 : 0;
+    }
   }
   __syncthreads();
-  for (int e = threadIdx.x; e < 64 * H_f; e += 256) {
-    const int h = e >> 6, tl = e & 63;
-    const int64_t tok = tok0 + tl;
-    if (tok >= tokens) continue;
-    const int64_t b = tok / L;
-    const int t = (int)(tok - b * L);
-    flags[((size_t)b * H_f + h) * L + t] = fl[h][tl];
+  for (int e = threadIdx.x; e < kFinTok * H_f; e += 256) {
+    const int hh = e / kFinTok, tl = e - hh * kFinTok;
+    const int64_t tk = tok0 + tl;
+    if (tk >= tokens) continue;
+    const int64_t b = tk / L;
+    const int t = (int)(tk - b * L);
+    flags[((size_t)b * H_f + hh) * L + t] = fl[hh][tl];
   }
 }
 
@@ -191,7 +202,7 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
     ag_tock(ctx, AG_K_GATE, s);
   }
   ag_tick(ctx, AG_K_GATE_FINALIZE, s);
-  hipLaunchKernelGGL(ag_gate_finalize_kernel, dim3((unsigned)((tokens + 63) / 64)), dim3(256), 0, s, partial,
+  hipLaunchKernelGGL(ag_gate_finalize_kernel, dim3((unsigned)((tokens + kFinTok - 1) / kFinTok)), dim3(256), 0, s, partial,
                      p.splits, p.tokens_pad, tokens, L, H_f, bias, thr, n_sink, logits, flags);
   ag_tock(ctx, AG_K_GATE_FINALIZE, s);
   return hipGetLastError();

@@ -70,6 +70,7 @@ struct ag_pf_plan {
   int32_t *order;        // [n_hy] head block at each position of a query-tile row
   int32_t *chunk_tiles;  // [1]   key tiles per chunk, from the measured amount of work
   int32_t *tickets;      // [n_items] chunks of an item that have stored their partial state
+  int32_t *kept;         // [units]  kept rows per unit, exchanged between the scan's workgroups
   int n_hy, HB, BM, n_items, n_split, slots, max_tiles;
 };
 

@@ -473,6 +473,14 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
     plan->tickets = ws.take<int32_t>((size_t)items);
   }
   if (plan->n_hy % 8 == 0 && plan->n_hy >= 16 && plan->n_hy <= 1024) plan->order = ws.take<int32_t>(plan->n_hy);
+  if (B * Hkv > 1024) {  // the planner holds the units' counts in LDS
+    plan->order = nullptr;
+    plan->chunk_tiles = nullptr;
+    plan->n_split = 1;
+    plan->tickets = nullptr;
+    *part = nullptr;
+  }
+  if (plan->order || plan->chunk_tiles) plan->kept = ws.take<int32_t>((size_t)B * Hkv);
 }
 
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
