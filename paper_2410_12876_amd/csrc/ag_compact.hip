@@ -1,7 +1,7 @@
 // Flag scan and KV stream compaction (Sec. 3.3: k, v of a token stay in the cache iff its flag is 1).
 //
 // Two kernels.  ag_flag_scan turns the byte flags of one (batch, KV head) unit into 64-bit keep masks (one
-// wave64 ballot per 64 tokens) and an exclusive prefix count per mask word.  ag_compact then gives every
+// wave64 ballot per 64 tokens) and an exclusive prefix count per mask word, 1024 tokens per workgroup.  ag_compact then gives every
 // wave one mask word: a lane's rank inside the word plus the word's prefix is the destination row, so the
 // surviving rows are written back-to-back (fully coalesced 16-byte stores) and evicted rows are never read.
 #include <string.h>
@@ -12,66 +12,83 @@ namespace {
 
 constexpr int kScanThreads = 256;
 
+constexpr int kSegWords = 16;  // mask words (1024 tokens) per scan workgroup
+
+// grid = (segments, units).  A workgroup builds the mask words of its 1024 tokens and needs the number of
+// kept tokens before them; it counts those itself (4 flags per load), so no workgroup waits for another.
 __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_t *__restrict__ flags, int L, int nw,
                                                                     uint64_t *__restrict__ words,
                                                                     int32_t *__restrict__ blk_off, ag_pf_plan plan,
                                                                     int num_units, int32_t *__restrict__ arrivals) {
-  extern __shared__ int32_t cnts[];  // nw counts, then 256 partial sums
-  int32_t *part = cnts + nw;
-  const int u = blockIdx.x;
+  __shared__ int32_t cnts[kSegWords];
+  __shared__ int32_t part[kScanThreads / 64];
+  const int u = blockIdx.y, seg = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint8_t *f = flags + (size_t)u * L;
-  constexpr int UN = 8;  // mask words per wave in flight (independent loads)
-  for (int w0 = wave * UN; w0 < nw; w0 += (kScanThreads / 64) * UN) {
-    uint8_t fb[UN];
+  const int w_first = seg * kSegWords;
+  const bool last_seg = seg == (int)gridDim.x - 1;
+
+  // this segment's flags first (the loads are independent of the count below)
+  constexpr int WPW = kSegWords / (kScanThreads / 64);  // words per wave
+  uint8_t fb[WPW];
 #pragma unroll
-    for (int j = 0; j < UN; ++j) {
-      const int t = (w0 + j) * 64 + lane;
-      fb[j] = (w0 + j < nw && t < L) ? f[t] : (uint8_t)0;
+  for (int j = 0; j < WPW; ++j) {
+    const int w = w_first + wave * WPW + j;
+    const int t = w * 64 + lane;
+    fb[j] = (w < nw && t < L) ? f[t] : (uint8_t)0;
+  }
+  // kept tokens before the segment
+  const int t_end = w_first * 64;  // <= L, a multiple of 1024
+  int before = 0;
+  if ((reinterpret_cast<uintptr_t>(f) & 3) == 0) {
+    const uint32_t *f4 = reinterpret_cast<const uint32_t *>(f);
+    for (int i = tid; i < t_end / 4; i += kScanThreads) {
+      const uint32_t x = f4[i];
+      before += __popc((((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u);  // non-zero bytes of x
     }
+  } else {
+    for (int i = tid; i < t_end; i += kScanThreads) before += f[i] != 0;
+  }
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o, 64);
+  if (lane == 0) part[wave] = before;
 #pragma unroll
-    for (int j = 0; j < UN; ++j) {
-      const uint64_t m = __ballot(fb[j] != 0);
-      if (lane == 0 && w0 + j < nw) {
-        words[(size_t)u * nw + w0 + j] = m;
-        cnts[w0 + j] = __popcll(m);
-      }
+  for (int j = 0; j < WPW; ++j) {
+    const int w = w_first + wave * WPW + j;
+    const uint64_t m = __ballot(fb[j] != 0);
+    if (lane == 0) {
+      cnts[wave * WPW + j] = __popcll(m);
+      if (w < nw) words[(size_t)u * nw + w] = m;
     }
   }
   __syncthreads();
-  // exclusive scan of cnts[0..nw): each thread owns a contiguous run of `per` words
-  const int per = (nw + kScanThreads - 1) / kScanThreads;
-  const int w0 = tid * per, w1 = min(nw, w0 + per);
-  int32_t sum = 0;
-  for (int w = w0; w < w1; ++w) sum += cnts[w];
-  part[tid] = sum;
-  __syncthreads();
-  for (int d = 1; d < kScanThreads; d <<= 1) {
-    int32_t add = tid >= d ? part[tid - d] : 0;
-    __syncthreads();
-    part[tid] += add;
-    __syncthreads();
-  }
-  int32_t run = part[tid] - sum;  // exclusive prefix of this thread's run
   int32_t *bo = blk_off + (size_t)u * (nw + 1);
-  for (int w = w0; w < w1; ++w) {
-    bo[w] = run;
-    run += cnts[w];
+  int32_t unit_total = 0;
+  if (tid == 0) {
+    int32_t run = 0;
+    for (int i = 0; i < kScanThreads / 64; ++i) run += part[i];
+    for (int j = 0; j < kSegWords; ++j) {
+      if (w_first + j < nw) bo[w_first + j] = run;
+      run += cnts[j];
+    }
+    if (last_seg) bo[nw] = run;
+    unit_total = run;
   }
-  if (tid == kScanThreads - 1) bo[nw] = part[tid];
 
   // ---- optional: prepare the prefill kernel's launch plan ----
-  if (plan.tickets)
-    for (int i = blockIdx.x * kScanThreads + tid; i < plan.n_items; i += gridDim.x * kScanThreads) plan.tickets[i] = 0;
+  if (plan.tickets) {
+    const int nb = gridDim.x * gridDim.y, bid = blockIdx.y * gridDim.x + blockIdx.x;
+    for (int i = bid * kScanThreads + tid; i < plan.n_items; i += nb * kScanThreads) plan.tickets[i] = 0;
+  }
   if (!plan.order && !plan.chunk_tiles) return;
   // The workgroup that arrives last turns the units' kept-row counts into the plan.  The counts cross
   // workgroups inside one launch, so they are written through and read past the caches (system-scope relaxed
   // accesses, complete before the arrival is counted) instead of paying for cache-wide fences.
+  if (!last_seg) return;  // a unit's last segment knows its total
   __shared__ int is_last;
   if (tid == 0) {
-    __hip_atomic_store(&plan.kept[u], part[kScanThreads - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(&plan.kept[u], unit_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    is_last = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1;
+    is_last = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.y - 1;
     if (is_last) __hip_atomic_store(arrivals, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
   }
   __syncthreads();
@@ -105,15 +122,12 @@ __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_
       const int64_t pos = min((t + 1) * plan.BM, L);
       steps += (int)(((int64_t)kept[uu] * pos / L + 63) / 64);
     }
+    for (int o = 32; o > 0; o >>= 1) steps += __shfl_xor(steps, o, 64);
     __syncthreads();
-    part[tid] = steps;
+    if (lane == 0) part[wave] = steps;
     __syncthreads();
-    for (int d = kScanThreads / 2; d > 0; d >>= 1) {
-      if (tid < d) part[tid] += part[tid + d];
-      __syncthreads();
-    }
     if (tid == 0) {
-      const int64_t total = (int64_t)part[0] * plan.HB;
+      const int64_t total = (int64_t)(part[0] + part[1] + part[2] + part[3]) * plan.HB;
       int ct = (int)((total + plan.slots - 1) / plan.slots);
       const int lo = (plan.max_tiles + plan.n_split - 1) / plan.n_split;
       ct = ct < lo ? lo : ct;
@@ -210,13 +224,12 @@ size_t ag_ws_scan_bytes(int units, int L) {
 hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
                                int32_t *blk_off, const ag_pf_plan *plan) {
   const int nw = ag_nwords(L);
-  const size_t shmem = (size_t)(nw + kScanThreads) * sizeof(int32_t);
   ag_pf_plan none;
   memset(&none, 0, sizeof(none));
   int32_t *arrivals = ctx->d_err + 16;  // zeroed at creation; the kernel leaves it at zero
   ag_tick(ctx, AG_K_FLAG_SCAN, s);
-  hipLaunchKernelGGL(ag_flag_scan_kernel, dim3(units), dim3(kScanThreads), shmem, s, flags, L, nw, words, blk_off,
-                     plan ? *plan : none, units, arrivals);
+  hipLaunchKernelGGL(ag_flag_scan_kernel, dim3((nw + kSegWords - 1) / kSegWords, units), dim3(kScanThreads), 0, s, flags,
+                     L, nw, words, blk_off, plan ? *plan : none, units, arrivals);
   ag_tock(ctx, AG_K_FLAG_SCAN, s);
   return hipGetLastError();
 }

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
   constexpr int LPR = D / EPL;            // lanes per row
   constexpr int GPW = 64 / LPR;           // rows per wave load
   constexpr int NST = 4 * GPW;            // online-softmax states per block
-  constexpr int UN = 4;                   // rows in flight per lane group
+  constexpr int UN = G <= 2 ? 8 : 4;      // rows in flight per lane group
   extern __shared__ int32_t smem[];
   int32_t *item_off = smem;               // [U+1]
   int32_t *scan = smem + (U + 1);         // [256]
@@ -261,16 +261,40 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
 #pragma unroll
   for (int w = 0; w < (D + 63) / 64; ++w) s_self += red[w];
 
+  // item records of this (batch, head), 64 at a time: lane j takes record i0 + j, the wave reduces the maximum
+  // and the sum, the weights go through LDS, and every thread then adds its column with independent loads
+  __shared__ float wts[64];
   const int i0 = item_off[u], i1 = item_off[u + 1];
-  float M = s_self;
-  for (int it = i0; it < i1; ++it) M = fmaxf(M, pm[(size_t)it * G + gg]);
-  float L = exp2f(s_self - M);
-  float A = L * vn;
-  for (int it = i0; it < i1; ++it) {
-    const size_t pr = (size_t)it * G + gg;
-    const float w = exp2f(pm[pr] - M);
-    L = fmaf(w, pl[pr], L);
-    A = fmaf(w, pacc[pr * D + d], A);
+  const int lane = d & 63;
+  float M = s_self, L = 1.f, A = vn;  // state so far: the new token alone, relative to M
+  for (int base = i0; base < i1; base += 64) {
+    const int n = min(64, i1 - base);
+    const size_t pr = (size_t)(base + lane) * G + gg;
+    const float mj = lane < n ? pm[pr] : -INFINITY;
+    const float lj = lane < n ? pl[pr] : 0.f;
+    float mb = mj;
+    for (int o = 32; o > 0; o >>= 1) mb = fmaxf(mb, __shfl_xor(mb, o, 64));
+    const float M_new = fmaxf(M, mb);
+    const float keep = exp2f(M - M_new);
+    const float wj = lane < n ? exp2f(mj - M_new) : 0.f;
+    float lsum = wj * lj;
+    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o, 64);
+    __syncthreads();  // wts of the previous batch are consumed
+    if (d < 64) wts[d] = wj;
+    __syncthreads();
+    M = M_new;
+    L = L * keep + lsum;
+    A *= keep;
+    const float *col = pacc + ((size_t)base * G + gg) * D + d;
+    int j = 0;
+    for (; j + 8 <= n; j += 8) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = col[(size_t)(j + e) * G * D];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) A = fmaf(wts[j + e], x[e], A);
+    }
+    for (; j < n; ++j) A = fmaf(wts[j], col[(size_t)j * G * D], A);
   }
   narrow1(A / L, &out[(size_t)bi * D + d]);
 

@@ -4,9 +4,10 @@
 // path runs it on MFMA (v_mfma_f32_32x32x16_bf16, N padded to 32): every wave owns MT x 32 tokens and a slice
 // of the K range, streams its feature rows with 16-byte loads that together cover whole 128-byte lines, and
 // takes the matching W fragments from a pre-packed copy that stays in L2.  K is split over the 4 waves of a
-// workgroup and, when there are few tokens, over several workgroups; partial sums go to the workspace and a
-// second kernel adds them in a fixed order (so flags are reproducible run to run), adds the bias, compares
-// with the logit-space threshold and writes the flags head-major.
+// workgroup.  With enough tokens one fused kernel does everything (ag_gate_fused_kernel).  With few tokens K is
+// also split over several workgroups; partial sums then go to the workspace and a second kernel adds them in a
+// fixed order (so flags are reproducible run to run), adds the bias, compares with the logit-space threshold and
+// writes the flags head-major.
 #include "ag_internal.h"
 
 namespace {
@@ -18,8 +19,10 @@ constexpr int kNP = 32;  // padded head count (MFMA N)
 
 // W [d_in, H_f] bf16 -> fragment order: [(chunk*4 + step)*64 + lane][8], lane = (n = lane%32, kb = lane/32),
 // element j = W[chunk*64 + kb*32 + step*8 + j][n]  (0 for n >= H_f).
-__global__ void ag_gate_pack_w(const uint16_t *__restrict__ w, int d_in, int H_f, uint16_t *__restrict__ wp) {
+__global__ void ag_gate_pack_w(const uint16_t *__restrict__ w, int d_in, int H_f, uint16_t *__restrict__ wp,
+                               int32_t *__restrict__ tickets, int n_tickets) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;  // one packed element
+  if (i < n_tickets) tickets[i] = 0;  // arrival counters of the fused kernel's K splits
   if (i >= d_in * kNP) return;
   const int j = i & 7, lane = (i >> 3) & 63, step = (i >> 9) & 3, chunk = i >> 11;
   const int n = lane & 31, kb = lane >> 5;
@@ -78,6 +81,109 @@ __global__ __launch_bounds__(256) void ag_gate_mfma_kernel(const uint16_t *__res
   for (int e = threadIdx.x; e < MT * 32 * 32; e += 256) {
     const int t = e >> 10, row = (e >> 5) & 31, col = e & 31;
     dst[e] = red[0][t][row][col] + red[1][t][row][col] + red[2][t][row][col] + red[3][t][row][col];
+  }
+}
+
+// One workgroup of 8 waves per 32 tokens and K split (grid.y splits; wave w takes 64-wide chunks w, w + 8, ... of
+// its split, four in flight), the 8 partial tiles added in wave order through LDS.  With one split the workgroup
+// goes on to bias, threshold, logits and head-major flags.  With several, each stores its 32x32 partial tile
+// (written through the caches, complete before its arrival is counted) and the split that arrives last adds all
+// of them in split order -- the same order whoever is last, so the flags are reproducible -- and finishes.
+constexpr int kFusedWaves = 8;
+__global__ __launch_bounds__(64 * kFusedWaves) void ag_gate_fused_kernel(
+    const uint16_t *__restrict__ x, const uint4 *__restrict__ wp, int64_t tokens, int d_in, int L, int H_f,
+    const float *__restrict__ bias, float thr, int n_sink, float *__restrict__ logits, uint8_t *__restrict__ flags,
+    float *__restrict__ partial, int32_t *__restrict__ tickets) {
+  __shared__ float red[kFusedWaves][32][33];
+  __shared__ uint8_t fl[kNP][32];
+  __shared__ int is_last;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = lane & 31, kb = lane >> 5;
+  const int64_t tok0 = (int64_t)blockIdx.x * 32;
+  const int nchunks = d_in / 64;
+  const int splits = gridDim.y, split = blockIdx.y;
+  const int c_lo = (int)((int64_t)nchunks * split / splits), c_hi = (int)((int64_t)nchunks * (split + 1) / splits);
+  int64_t tok = tok0 + m;
+  if (tok >= tokens) tok = tokens - 1;  // clamp: the row is read but its result is never written
+  const uint4 *row = reinterpret_cast<const uint4 *>(x + (size_t)tok * d_in + kb * 32);
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  constexpr int PF = 4;
+  for (int c0 = c_lo + wave; c0 < c_hi; c0 += kFusedWaves * PF) {
+    uint4 a[PF][4], b[PF][4];
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+      const int c = c0 + kFusedWaves * p;
+      if (c < c_hi) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) a[p][s] = row[c * 8 + s];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) b[p][s] = wp[((size_t)c * 4 + s) * 64 + lane];
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+      if (c0 + kFusedWaves * p < c_hi) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[p][s]),
+                                                        __builtin_bit_cast(bf16x8, b[p][s]), acc, 0, 0, 0);
+      }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[wave][8 * (r >> 2) + 4 * kb + (r & 3)][m] = acc[r];
+  __syncthreads();
+  // element e = (token row e / 32, head e % 32); thread t owns e = t and t + 512
+  float v[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int e = threadIdx.x + 64 * kFusedWaves * i;
+    v[i] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) v[i] += red[w][e >> 5][e & 31];
+  }
+  if (splits > 1) {
+    float *tile = partial + (size_t)blockIdx.x * splits * 1024;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      __hip_atomic_store(&tile[split * 1024 + threadIdx.x + 64 * kFusedWaves * i], v[i], __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_SYSTEM);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+      is_last = __hip_atomic_fetch_add(&tickets[blockIdx.x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
+    __syncthreads();
+    if (!is_last) return;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      float sum = 0.f;
+      for (int sp = 0; sp < splits; ++sp) {
+        const float other = __hip_atomic_load(&tile[sp * 1024 + threadIdx.x + 64 * kFusedWaves * i], __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_SYSTEM);
+        sum += sp == split ? v[i] : other;
+      }
+      v[i] = sum;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int e = threadIdx.x + 64 * kFusedWaves * i;
+    const int rw = e >> 5, h = e & 31;
+    const int64_t tk = tok0 + rw;
+    if (h < H_f && tk < tokens) {
+      const float val = v[i] + bias[h];
+      if (logits) logits[(size_t)tk * H_f + h] = val;
+      fl[h][rw] = (val > thr || (int)(tk % L) < n_sink) ? 1 : 0;
+    }
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 32 * H_f; e += 64 * kFusedWaves) {
+    const int h = e >> 5, rw = e & 31;
+    const int64_t tk = tok0 + rw;
+    if (tk >= tokens) continue;
+    const int64_t b = tk / L;
+    flags[((size_t)b * H_f + h) * L + (tk - b * L)] = fl[h][rw];
   }
 }
 
@@ -172,7 +278,8 @@ size_t ag_ws_gate_bytes(int64_t tokens, int d_in, int H_f, ag_dtype dt) {
   const int64_t tokens_pad = (tokens + 63) / 64 * 64;
   const size_t part = ag_align256((size_t)16 * tokens_pad * kNP * sizeof(float));
   const size_t pack = dt == AG_BF16 ? ag_align256((size_t)d_in * kNP * 2) : 0;
-  return part + pack;
+  const size_t tickets = ag_align256((size_t)(tokens / 32 + 1) * sizeof(int32_t));  // fused kernel's K splits
+  return part + pack + tickets;
 }
 
 hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype dt, int B, int L, int d_in,
@@ -180,12 +287,29 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
                           uint8_t *flags, ws_cursor &ws) {
   const int64_t tokens = (int64_t)B * L;
   const gate_plan p = plan_gate(tokens, d_in, dt, ctx->num_cu);
-  float *partial = ws.take<float>((size_t)p.splits * p.tokens_pad * kNP);
+  const int64_t tiles32 = (tokens + 31) / 32;
+  const bool fused = dt == AG_BF16 && tiles32 >= ctx->num_cu / 4;  // enough token tiles: one fused kernel
+  int fsplits = 1;
+  if (fused) {  // K splits until the chip is covered, each wave keeping at least 2 chunks
+    while (tiles32 * fsplits < ctx->num_cu && d_in / 64 / (fsplits * 2) >= 2 * kFusedWaves && fsplits < 8) fsplits *= 2;
+  }
+  float *partial = fused ? (fsplits > 1 ? ws.take<float>((size_t)tiles32 * fsplits * 1024) : nullptr)
+                         : ws.take<float>((size_t)p.splits * p.tokens_pad * kNP);
+  int32_t *tickets = fused && fsplits > 1 ? ws.take<int32_t>((size_t)tiles32) : nullptr;
   uint16_t *wp = dt == AG_BF16 ? ws.take<uint16_t>((size_t)d_in * kNP) : nullptr;
   if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
   if (dt == AG_BF16) {
     const int n = d_in * kNP;
-    hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp);
+    hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp,
+                       tickets, tickets ? (int)tiles32 : 0);
+    if (fused) {
+      ag_tick(ctx, AG_K_GATE, s);
+      hipLaunchKernelGGL(ag_gate_fused_kernel, dim3((unsigned)tiles32, fsplits), dim3(64 * kFusedWaves), 0, s,
+                         (const uint16_t *)feat, (const uint4 *)wp, tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags,
+                         partial, tickets);
+      ag_tock(ctx, AG_K_GATE, s);
+      return hipGetLastError();
+    }
     const dim3 grid(p.tiles, p.splits);
     ag_tick(ctx, AG_K_GATE, s);
     if (p.mt == 2)
