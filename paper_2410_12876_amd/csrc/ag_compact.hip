@@ -177,24 +177,32 @@ __global__ __launch_bounds__(256) void ag_compact_kernel(const uint4 *__restrict
   constexpr int UN = 4;          // independent rows in flight per lane group
   const int sub = lane / LPR, seg0 = lane % LPR;
   const size_t src_unit = (size_t)u * L * row_vec;
+  // Loads are unconditional (a row index past the word's last kept row re-reads that last row) so that all UN row
+  // pairs stay in registers and in flight together; only the stores are predicated.
   for (int c0 = 0; c0 < n; c0 += RPI * UN) {
+    size_t src[UN];
+#pragma unroll
+    for (int j = 0; j < UN; ++j) {
+      const int c = c0 + j * RPI + sub;
+      src[j] = src_unit + (size_t)(w * 64 + sel[wave][c < n ? c : n - 1]) * row_vec;
+    }
     for (int seg = seg0; seg < row_vec; seg += LPR) {
       uint4 kk[UN], vv[UN];
-      bool ok[UN];
 #pragma unroll
       for (int j = 0; j < UN; ++j) {
-        const int c = c0 + j * RPI + sub;
-        ok[j] = c < n && base + c < cap;
-        if (ok[j]) {
-          const size_t src = src_unit + (size_t)(w * 64 + sel[wave][c]) * row_vec + seg;
-          kk[j] = k[src];
-          vv[j] = v[src];
-        }
+        kk[j] = k[src[j] + seg];
+        vv[j] = v[src[j] + seg];
+      }
+      // Keeps the compiler from sinking each load into its predicated store, which would serialise the rows.
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        asm volatile("" : "+v"(kk[j].x), "+v"(kk[j].y), "+v"(kk[j].z), "+v"(kk[j].w));
+        asm volatile("" : "+v"(vv[j].x), "+v"(vv[j].y), "+v"(vv[j].z), "+v"(vv[j].w));
       }
 #pragma unroll
       for (int j = 0; j < UN; ++j) {
         const int c = c0 + j * RPI + sub;
-        if (ok[j]) {
+        if (c < n && base + c < cap) {
           const size_t dst = (size_t)(r0 + base + c) * row_vec + seg;
           kc[dst] = kk[j];
           vc[dst] = vv[j];
