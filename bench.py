@@ -132,7 +132,7 @@ def prefill_leg(args, torch, ag, W):
         "keep_ratio": float(fl.mean()),
         "roofline": {"kernel": "ag_prefill_d128_kernel<1>", "bound": "mfma", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "flops_per_launch": flops, "visible_pairs": pairs,
+                     "traffic": TRAFFIC_BYTES.get(("prefill", L)) if B == 1 else None, "flops_per_launch": flops, "visible_pairs": pairs,
                      "avg_launch_ms": pf_ms},
         "compact_gbs": (2 * 2 * kept_rows * D * 2 + fl.size + 4 * kept_rows) / (per_kernel["compact"] * 1e-3) / 1e9,
         "gate_gbs": (B * L * d * 2) / (per_kernel["gate"] * 1e-3) / 1e9,
@@ -190,7 +190,8 @@ def decode_leg(args, torch, ag, W):
         "steps": steps, "ms_per_step": (t1 - t0) / steps * 1e3,
         "kernel_ms": {"decode_partial": part_ms, "decode_merge": merge_ms},
         "roofline": {"kernel": "ag_decode_partial_kernel<bf16,128,1>", "bound": "hbm", "achieved": ach,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC_BYTES.get(("decode", B, steps)),
                      "bytes_per_launch": bytes_per_step, "avg_launch_ms": part_ms},
         "config": {"workload": wl.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D,
                    "mean_len": float(rows_per_step / (B * Hkv)), "keep_vs_4096": float(rows_per_step / (B * Hkv) / 4096)},
@@ -219,6 +220,15 @@ def cpu_baseline(wl, W):
     t = (t_mid - t0) + (t1 - t_mid2)
     return {"value": wl.B * L / t, "unit": "tokens/s", "cores": min(oracle.threads(), wl.B * H), "kind": "oracle",
             "sample": "one whole config-2 step (all %d heads, L=%d): %.2f s" % (H, L, t), "seconds_sample": t}
+
+
+# HBM bytes per launch from the rocprofv3 counter passes summarised in
+# profiles/bench_cfg2_prefill_cfg3_decode_hbm_traffic.md (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE, in KiB, the
+# factors calibrated on the 1 GiB copy kernel); they hold for the default workloads only.
+TRAFFIC_BYTES = {
+    ("prefill", 4096): int((2.0 * 93093 + 45481) * 1024),
+    ("decode", 32, 256): int((2.0 * 576400 + 5513) * 1024),
+}
 
 
 def machine_context(torch, ag):
