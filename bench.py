@@ -49,7 +49,7 @@ def visible_pairs(flags: np.ndarray, G: int) -> int:
 
 
 def prefill_leg(args, torch, ag, W):
-    wl = W.config2(L=args.seq_len)
+    wl = W.config2(L=args.seq_len, keep=None if args.keep is None else np.full(32, args.keep))
     B, L, Hq, Hkv, D, d = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D, wl.d_model
     G = Hq // Hkv
     U = B * Hkv
@@ -132,12 +132,12 @@ def prefill_leg(args, torch, ag, W):
         "keep_ratio": float(fl.mean()),
         "roofline": {"kernel": "ag_prefill_d128_kernel<1>", "bound": "mfma", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": TRAFFIC_BYTES.get(("prefill", L)) if B == 1 else None, "flops_per_launch": flops, "visible_pairs": pairs,
+                     "traffic": TRAFFIC_BYTES.get(("prefill", L)) if args.keep is None else None, "flops_per_launch": flops, "visible_pairs": pairs,
                      "avg_launch_ms": pf_ms},
         "compact_gbs": (2 * 2 * kept_rows * D * 2 + fl.size + 4 * kept_rows) / (per_kernel["compact"] * 1e-3) / 1e9,
         "gate_gbs": (B * L * d * 2) / (per_kernel["gate"] * 1e-3) / 1e9,
         "config": {"workload": wl.name, "B": B, "L": L, "d_model": d, "Hq": Hq, "Hkv": Hkv, "D": D,
-                   "keep": "per-head U[0.2,0.9], mean %.3f" % fl.mean(),
+                   "keep": ("per-head U[0.2,0.9]" if args.keep is None else "every head %.2f" % args.keep) + ", mean %.3f" % fl.mean(),
                    "launch": "hip graph replay" if graph is not None else "eager"},
     }
     ctx.close()
@@ -258,6 +258,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--seq-len", type=int, default=4096)
+    ap.add_argument("--keep", type=float, default=None,
+                    help="one keep ratio for every head instead of config 2's per-head U[0.2, 0.9]")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-batch", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching it eagerly")
