@@ -84,6 +84,24 @@ def prefill_attn(q, k, v, flags, scale: float, n_recent: int = 1) -> np.ndarray:
     return out
 
 
+def prefill_rows(q, k, v, flags, scale: float, rows, n_recent: int = 1) -> np.ndarray:
+    """prefill_attn restricted to the query positions `rows` (same for every head):
+    out f64 [B,Hq,len(rows),D].  For sampled checks of problems too large to compute whole."""
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    flags = np.ascontiguousarray(flags, dtype=np.uint8)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, L, D) and v.shape == k.shape and flags.shape == (B, Hkv, L)
+    assert Hq % Hkv == 0 and n_recent >= 1 and rows.ndim == 1
+    assert rows.size == 0 or (rows.min() >= 0 and rows.max() < L)
+    out = np.empty((B, Hq, rows.size, D), dtype=np.float64)
+    lib().ag_oracle_prefill_rows(_p(q), _p(k), _p(v), _p(flags), C.c_int(B), C.c_int(L), C.c_int(Hq),
+                                 C.c_int(Hkv), C.c_int(D), C.c_double(scale), C.c_int(n_recent), _p(rows),
+                                 C.c_int(rows.size), _p(out))
+    return out
+
+
 @dataclass
 class Cache:
     """Ragged per-(batch, KV head) cache.  k/v hold rows in the storage dtype given to

@@ -84,10 +84,36 @@ static inline int visible(const uint8_t *f, int j, int t, int n_recent) {
 }
 
 /*
+ * One output row of Eq. 2 under the mask of Eq. 5: query row j of one head against the
+ * keys/values 0..j of its KV head.  Q, K, V point at the head's [L, D] blocks, f at the
+ * head's flags, z is scratch for L scores, o receives D values.  Masked columns contribute
+ * exactly zero (the "large constant INF" of Eq. 2 taken as infinity).
+ */
+static void attn_row(const float *Q, const float *K, const float *V, const uint8_t *f, int j, int D,
+                     double scale, int n_recent, double *z, double *o) {
+  double m = -INFINITY;
+  for (int t = 0; t <= j; ++t) {
+    if (!visible(f, j, t, n_recent)) continue;
+    double s = 0.0;
+    for (int c = 0; c < D; ++c) s += (double)Q[(size_t)j * D + c] * (double)K[(size_t)t * D + c];
+    z[t] = s * scale;
+    if (z[t] > m) m = z[t];
+  }
+  double denom = 0.0;
+  for (int c = 0; c < D; ++c) o[c] = 0.0;
+  for (int t = 0; t <= j; ++t) {
+    if (!visible(f, j, t, n_recent)) continue;
+    const double p = exp(z[t] - m);
+    denom += p;
+    for (int c = 0; c < D; ++c) o[c] += p * (double)V[(size_t)t * D + c];
+  }
+  for (int c = 0; c < D; ++c) o[c] /= denom;
+}
+
+/*
  * Flag-masked causal attention, Eq. 2 with the mask of Eq. 5, one head at a time.
  *   q [B, Hq, L, D], k/v [B, Hkv, L, D], flags [B, Hkv, L], out [B, Hq, L, D] (fp64)
- * Query head i uses KV head i / (Hq / Hkv).  Masked columns contribute exactly zero
- * (the "large constant INF" of Eq. 2 taken as infinity).
+ * Query head i uses KV head i / (Hq / Hkv).
  */
 void ag_oracle_prefill_attn(const float *q, const float *k, const float *v, const uint8_t *flags,
                             int B, int L, int Hq, int Hkv, int D, double scale, int n_recent,
@@ -103,26 +129,33 @@ void ag_oracle_prefill_attn(const float *q, const float *k, const float *v, cons
       const uint8_t *f = flags + ((size_t)b * Hkv + g) * L;
       double *O = out + ((size_t)b * Hq + i) * L * D;
       double *z = (double *)malloc(sizeof(double) * (size_t)L);
-      for (int j = 0; j < L; ++j) {
-        double m = -INFINITY;
-        for (int t = 0; t <= j; ++t) {
-          if (!visible(f, j, t, n_recent)) continue;
-          double s = 0.0;
-          for (int c = 0; c < D; ++c) s += (double)Q[(size_t)j * D + c] * (double)K[(size_t)t * D + c];
-          z[t] = s * scale;
-          if (z[t] > m) m = z[t];
-        }
-        double denom = 0.0;
-        for (int c = 0; c < D; ++c) O[(size_t)j * D + c] = 0.0;
-        for (int t = 0; t <= j; ++t) {
-          if (!visible(f, j, t, n_recent)) continue;
-          const double p = exp(z[t] - m);
-          denom += p;
-          for (int c = 0; c < D; ++c) O[(size_t)j * D + c] += p * (double)V[(size_t)t * D + c];
-        }
-        for (int c = 0; c < D; ++c) O[(size_t)j * D + c] /= denom;
-      }
+      for (int j = 0; j < L; ++j) attn_row(Q, K, V, f, j, D, scale, n_recent, z, O + (size_t)j * D);
       free(z);
+    }
+  }
+}
+
+/*
+ * The same rows, but only the query positions rows[0..n_rows) of every head (for checking
+ * samples of a problem too large to compute whole).  out [B, Hq, n_rows, D] (fp64).
+ */
+void ag_oracle_prefill_rows(const float *q, const float *k, const float *v, const uint8_t *flags,
+                            int B, int L, int Hq, int Hkv, int D, double scale, int n_recent,
+                            const int32_t *rows, int n_rows, double *out) {
+  const int G = Hq / Hkv;
+#pragma omp parallel for collapse(3) schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b) {
+    for (int i = 0; i < Hq; ++i) {
+      for (int r = 0; r < n_rows; ++r) {
+        const int g = i / G;
+        const float *Q = q + ((size_t)b * Hq + i) * L * D;
+        const float *K = k + ((size_t)b * Hkv + g) * L * D;
+        const float *V = v + ((size_t)b * Hkv + g) * L * D;
+        const uint8_t *f = flags + ((size_t)b * Hkv + g) * L;
+        double *z = (double *)malloc(sizeof(double) * (size_t)L);
+        attn_row(Q, K, V, f, rows[r], D, scale, n_recent, z, out + (((size_t)b * Hq + i) * n_rows + r) * D);
+        free(z);
+      }
     }
   }
 }

@@ -115,6 +115,24 @@ def test_recent_window_vs_dense_mask(n_recent):
     np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-13)
 
 
+@pytest.mark.parametrize("n_recent", [1, 4])
+def test_sampled_rows_vs_dense_mask_with_gqa(n_recent):
+    """prefill_rows (used for sampled checks of large problems) against Eq. 2/5 written densely: GQA head
+    mapping, an unsorted row list with a repeat, first and last row."""
+    B, Hq, Hkv, L, D = 2, 6, 2, 53, 16
+    q, k, v = rnd(40, B, Hq, L, D), rnd(41, B, Hkv, L, D), rnd(42, B, Hkv, L, D)
+    flags = (np.random.default_rng(43).random((B, Hkv, L)) < 0.4).astype(np.uint8)
+    rows = np.array([52, 0, 17, 17, 31, 1])
+    out = oracle.prefill_rows(q, k, v, flags, 0.25, rows, n_recent=n_recent)
+    assert out.shape == (B, Hq, len(rows), D)
+    for b in range(B):
+        for i in range(Hq):
+            g = i // (Hq // Hkv)
+            want = dense_masked_attention(q[b, i], k[b, g], v[b, g], eq5_mask(flags[b, g], n_recent), 0.25)
+            np.testing.assert_allclose(out[b, i], want[rows], rtol=1e-12, atol=1e-13)
+    assert oracle.prefill_rows(q, k, v, flags, 0.25, np.zeros(0, dtype=np.int32)).shape == (B, Hq, 0, D)
+
+
 # ------------------------------------------------------------------ special cases -> library routines
 def test_all_kept_is_causal_sdpa():
     B, H, L, D = 2, 3, 50, 32
