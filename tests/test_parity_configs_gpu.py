@@ -1,0 +1,265 @@
+"""Full-size parity runs of configs 3, 4 and 5, the launch shapes of the tuned kernels, reproducibility and
+HIP-graph replay.  Problems too large for the oracle to compute whole are checked on sampled query rows of every
+head (oracle.prefill_rows computes a chosen row from the definition); integer results are compared whole."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2410_12876_amd as ag
+import workloads as W
+from gpu_util import (DEV, attn_error, attn_rms_error, attn_tolerance, cache_from_host, dev, ensure_built, host_bits,
+                      host_f32, make_ctx, new_cache)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    ensure_built()
+
+
+def sample_rows(L, seed, n_random=8):
+    """Query positions that include the first/last rows and both sides of the 64- and 128-row tile edges."""
+    fixed = [0, 1, 62, 63, 64, 65, 127, 128, 129, 255, 256, L // 2 - 1, L // 2, L - 130, L - 129, L - 128, L - 65, L - 64,
+             L - 2, L - 1]
+    rnd = np.random.default_rng(seed).integers(0, L, n_random).tolist()
+    return np.array(sorted({r for r in fixed + rnd if 0 <= r < L}), dtype=np.int32)
+
+
+def check_sampled_rows(got_f32, q, k, v, flags, scale, rows, what):
+    ref = oracle.prefill_rows(q.f32, k.f32, v.f32, flags, scale, rows)
+    got = got_f32[:, :, rows, :]
+    err, tol = attn_error("bf16", got, ref), attn_tolerance("bf16", ref)
+    rel = attn_rms_error(got, ref)
+    print("%s: %d rows x %d heads: max-abs err / row RMS %.3g (tol %.3g), RMS err / RMS %.3g" %
+          (what, len(rows), got.shape[0] * got.shape[1], err, tol, rel))
+    assert np.isfinite(got).all() and err <= tol and rel <= 5e-3
+
+
+def compact_and_check(ctx, wl, dk, dv, dflags, flags_np, cap):
+    """ag_compact_kv into per-unit slabs of `cap` rows; rows, idx and len compared bit for bit."""
+    U = wl.B * wl.Hkv
+    ro = oracle.slab_row_off(U, cap)
+    cache = new_cache(wl.B, wl.Hkv, wl.D, torch.bfloat16, ro)
+    ag.ag_compact_kv(ctx, dk, dv, dflags, 0, cache)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    ref, over = oracle.compact_kv(wl.k.storage, wl.v.storage, flags_np, ro)
+    assert over == 0
+    assert np.array_equal(cache.len.cpu().numpy(), ref.len)
+    gk, gv, gi = host_bits(cache.k), host_bits(cache.v), cache.idx.cpu().numpy()
+    for u in range(U):
+        a, n = int(ro[u]), int(ref.len[u])
+        assert np.array_equal(gk[a:a + n], ref.k[a:a + n]) and np.array_equal(gv[a:a + n], ref.v[a:a + n])
+        assert np.array_equal(gi[a:a + n], ref.idx[a:a + n])
+    return cache, ref, ro
+
+
+def decode_and_check(ctx, wl, cache, ref_bits: "oracle.Cache", ro, steps, seed, keep_prob):
+    """`steps` decode steps on the cache the compaction left, against the oracle's decode on the same rows."""
+    B, Hq, Hkv, D = wl.B, wl.Hq, wl.Hkv, wl.D
+    ref = oracle.Cache(W.bf16_bits_to_f32(ref_bits.k), W.bf16_bits_to_f32(ref_bits.v), ref_bits.idx.copy(), ro.copy(),
+                       ref_bits.len.copy())
+    out = torch.empty(B, Hq, D, dtype=torch.bfloat16, device=DEV)
+    g = np.random.default_rng(seed)
+    for s in range(steps):
+        q, kn, vn = (W.store(g.standard_normal(shape).astype(np.float32), "bf16")
+                     for shape in ((B, Hq, D), (B, Hkv, D), (B, Hkv, D)))
+        nf = None if keep_prob is None else (g.random((B, Hkv)) < keep_prob).astype(np.uint8)
+        ag.ag_decode_attn(ctx, dev(q), dev(kn), dev(vn), None if nf is None else dev(nf), wl.L + s, wl.scale, cache, out)
+        want, dropped = oracle.decode_step(q.f32, kn.f32, vn.f32, nf, wl.L + s, ref, wl.scale)
+        got = host_f32(out)
+        assert dropped == 0 and np.isfinite(got).all()
+        assert attn_error("bf16", got, want) <= attn_tolerance("bf16", want)
+        assert np.array_equal(cache.len.cpu().numpy(), ref.len)
+    ctx.poll_error()
+
+
+# ------------------------------------------------------------------------------------------------ config 4
+def test_config4_full_size_gqa_long_prompt():
+    """Llama-3-8B layer shape (32 query / 8 KV heads, L = 32768, run-structured flags, keep 0.3): compaction whole,
+    prefill on sampled rows of all 32 query heads, then 4 decode steps on the 8 long caches."""
+    wl = W.config4()
+    B, L, Hq, Hkv, D = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D
+    steps = 4
+    ctx = make_ctx(B, L, Hq, Hkv, D, ag.AG_BF16, cache_rows=B * Hkv * (L + steps))
+    dq, dk, dv, df = dev(wl.q), dev(wl.k), dev(wl.v), dev(wl.flags)
+    cache, ref, ro = compact_and_check(ctx, wl, dk, dv, df, wl.flags, L + steps)
+    print("cfg4 keep %.3f" % wl.flags.mean())
+    out = torch.empty_like(dq)
+    ag.ag_prefill_attn(ctx, dq, dk, dv, df, wl.scale, cache, out)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    check_sampled_rows(host_f32(out), wl.q, wl.k, wl.v, wl.flags, wl.scale, sample_rows(L, 44, 12), "cfg4 prefill")
+    decode_and_check(ctx, wl, cache, ref, ro, steps, 45, 0.5)
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------------ config 5
+@pytest.mark.parametrize("layer", [0, 31])
+def test_config5_layer_full_size(layer):
+    """One layer of the 32-layer stack at full size (B=16, L=2048, 32 heads): first layer (keep 0.9) and last
+    layer (keep 0.1, several fully evicted heads).  Gate whole, compaction whole, prefill on sampled rows of all
+    512 heads (fully evicted heads: whole output equals V bit for bit), 2 decode steps over all 512 caches."""
+    wl = W.config5_layer(layer)
+    B, L, H, D, d = wl.B, wl.L, wl.Hq, wl.D, wl.d_model
+    steps = 2
+    ctx = make_ctx(B, L, H, H, D, ag.AG_BF16, d_in=d, cache_rows=B * H * (L + steps))
+    flags = torch.empty(B, H, L, dtype=torch.uint8, device=DEV)
+    logits = torch.empty(B, L, H, dtype=torch.float32, device=DEV)
+    ag.ag_gate(ctx, dev(wl.x), dev(wl.w_gate), dev(wl.bias), wl.tau, wl.n_sink, logits, flags)
+    torch.cuda.synchronize()
+    ref_logits, ref_flags = oracle.gate(wl.x.f32, wl.w_gate.f32, wl.bias, wl.tau, wl.n_sink)
+    live = ~wl.extra["dead_heads"]
+    assert np.abs(logits.cpu().numpy() - ref_logits)[:, :, live].max() <= 2e-4
+    near = (np.abs(ref_logits - oracle.logit_threshold(wl.tau)) < 1e-3).transpose(0, 2, 1)
+    fl = flags.cpu().numpy()
+    assert np.array_equal(fl[~near], ref_flags[~near])
+    print("cfg5 layer %d: keep %.3f, %d logits within 1e-3 of the threshold (excluded), %d of them differ, %d dead heads"
+          % (layer, fl.mean(), int(near.sum()), int((fl != ref_flags).sum()), int((~live).sum())))
+    assert (fl[:, ~live] == 0).all()
+    # later stages are checked on the flags the HIP gate produced
+    dq, dk, dv = dev(wl.q), dev(wl.k), dev(wl.v)
+    cache, ref, ro = compact_and_check(ctx, wl, dk, dv, flags, fl, L + steps)
+    if (~live).any():
+        assert (ref.len.reshape(B, H)[:, ~live] == 0).all()
+    out = torch.empty_like(dq)
+    ag.ag_prefill_attn(ctx, dq, dk, dv, flags, wl.scale, cache, out)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    for h in np.nonzero(~live)[0]:
+        assert torch.equal(out[:, h], dv[:, h])            # fully evicted head: every row is its own value
+    check_sampled_rows(host_f32(out), wl.q, wl.k, wl.v, fl, wl.scale, sample_rows(L, 50 + layer, 4),
+                       "cfg5 layer %d prefill" % layer)
+    decode_and_check(ctx, wl, cache, ref, ro, steps, 60 + layer, 0.5)
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------------ config 3
+def test_config3_full_batch():
+    """Config 3 at its full batch (B=32: 1024 ragged caches, 2.3 M rows) for 3 steps, every unit checked."""
+    from test_parity_gpu import check_decode
+    wl = W.config3(B=32, steps=3)
+    worst = check_decode(wl, 3, 0.5, "bf16")
+    print("cfg3 (B=32) worst err/tol %.3f" % worst)
+
+
+# ------------------------------------------------------------------------------- launch shapes of the D=128 kernel
+def _prefill_case(B, Hq, Hkv, L, flags, seed, with_cache=True):
+    D = 128
+    g = np.random.default_rng(seed)
+    q, k, v = (W.store(g.standard_normal(s).astype(np.float32), "bf16")
+               for s in ((B, Hq, L, D), (B, Hkv, L, D), (B, Hkv, L, D)))
+    ctx = make_ctx(B, L, Hq, Hkv, D, ag.AG_BF16)
+    dq, dk, dv, df = dev(q), dev(k), dev(v), dev(flags)
+    out = torch.empty_like(dq)
+    cache = None
+    if with_cache:
+        cache = new_cache(B, Hkv, D, torch.bfloat16, oracle.slab_row_off(B * Hkv, L))
+        ag.ag_compact_kv(ctx, dk, dv, df, 0, cache)
+    ag.ag_prefill_attn(ctx, dq, dk, dv, df, 1.0 / math.sqrt(D), cache, out)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    ctx.close()
+    return q, k, v, out
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,L", [
+    ("split in two key chunks, balanced order", 1, 16, 16, 2048),
+    ("split, heads not a multiple of 8 (no reordering)", 1, 3, 3, 4096),
+    ("large launch, no split", 4, 32, 32, 2048),
+    ("more than 1024 units (plan off)", 36, 32, 32, 256),
+    ("GQA split", 1, 32, 8, 2048),
+    ("ragged length", 2, 16, 4, 1987),
+])
+def test_prefill_d128_launch_shapes(name, B, Hq, Hkv, L):
+    """The workgroup-to-item mapping, the head order and the key-chunk split change with the launch size; every
+    variant must give the same rows.  Keep ratios differ strongly between heads (0.05 .. 1.0) so that chunking and
+    ordering see uneven work; head 0 keeps everything, head 1 nothing."""
+    g = np.random.default_rng(70)
+    keep = np.linspace(1.0, 0.05, Hkv)[None, :, None]
+    flags = (g.random((B, Hkv, L)) < keep).astype(np.uint8)
+    flags[:, 0] = 1
+    if Hkv > 1:
+        flags[:, 1] = 0
+    q, k, v, out = _prefill_case(B, Hq, Hkv, L, flags, 71)
+    check_sampled_rows(host_f32(out), q, k, v, flags, 1.0 / math.sqrt(128), sample_rows(L, 72, 6), name)
+    if Hkv > 1:
+        G = Hq // Hkv
+        assert torch.equal(out[:, G:2 * G], dev(v)[:, 1:2].expand(-1, G, -1, -1))
+
+
+def test_prefill_and_gate_are_reproducible_bit_for_bit():
+    """Two runs of the split/merge prefill and of the K-split gate give identical bits (fixed merge orders)."""
+    B, H, L = 1, 32, 4096
+    g = np.random.default_rng(80)
+    flags = (g.random((B, H, L)) < np.linspace(0.2, 0.9, H)[None, :, None]).astype(np.uint8)
+    a = _prefill_case(B, H, H, L, flags, 81)[3]
+    b = _prefill_case(B, H, H, L, flags, 81)[3]
+    assert torch.equal(a, b)
+    c = _prefill_case(B, H, H, L, flags, 81, with_cache=False)[3]      # internal compaction: same rows, same result
+    assert torch.equal(a, c)
+    x = W.store(g.standard_normal((B, L, 4096)).astype(np.float32) * 0.5, "bf16")
+    w = W.store(g.standard_normal((4096, H)).astype(np.float32) / 64.0, "bf16")
+    bias = np.zeros(H, np.float32)
+    res = []
+    for _ in range(2):
+        ctx = make_ctx(B, L, H, H, 128, ag.AG_BF16, d_in=4096)
+        lo = torch.empty(B, L, H, dtype=torch.float32, device=DEV)
+        fo = torch.empty(B, H, L, dtype=torch.uint8, device=DEV)
+        ag.ag_gate(ctx, dev(x), dev(w), dev(bias), 0.5, 0, lo, fo)
+        torch.cuda.synchronize()
+        ctx.close()
+        res.append((lo, fo))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+
+
+# ------------------------------------------------------------------------------------------------ HIP graph
+def test_whole_step_replays_from_a_hip_graph():
+    """gate -> compaction -> prefill -> decode captured once in a HIP graph: several replays, with eager work of
+    the same library between them, must reproduce the eager step bit for bit (the kernels re-zero their own
+    counters, nothing is cleared by a memset node)."""
+    B, H, L, D, d = 1, 16, 2048, 128, 1024
+    g = np.random.default_rng(90)
+    x = dev(W.store(g.standard_normal((B, L, d)).astype(np.float32) * 0.5, "bf16"))
+    w = dev(W.store(g.standard_normal((d, H)).astype(np.float32) / 32.0, "bf16"))
+    bias = dev(np.linspace(-0.3, 0.3, H).astype(np.float32))
+    q, k, v = (dev(W.store(g.standard_normal((B, H, L, D)).astype(np.float32), "bf16")) for _ in range(3))
+    dq, dk, dv = (dev(W.store(g.standard_normal((B, H, D)).astype(np.float32), "bf16")) for _ in range(3))
+    cap = L + 4
+    ctx = make_ctx(B, L, H, H, D, ag.AG_BF16, d_in=d, cache_rows=B * H * cap)
+    cache = new_cache(B, H, D, torch.bfloat16, oracle.slab_row_off(B * H, cap))
+    flags = torch.empty(B, H, L, dtype=torch.uint8, device=DEV)
+    out, dout = torch.empty_like(q), torch.empty_like(dq)
+
+    def step():
+        ag.ag_gate(ctx, x, w, bias, 0.5, 0, None, flags)
+        ag.ag_compact_kv(ctx, k, v, flags, 0, cache)
+        ag.ag_prefill_attn(ctx, q, k, v, flags, 1.0 / math.sqrt(D), cache, out)
+        ag.ag_decode_attn(ctx, dq, dk, dv, None, L, 1.0 / math.sqrt(D), cache, dout)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (flags, out, dout, cache.len, cache.k, cache.idx)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for r in range(4):
+        for t in (flags, out, dout, cache.len):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((flags, out, dout, cache.len, cache.k, cache.idx), ref):
+            assert torch.equal(got, want), "replay %d differs from the eager step" % r
+        step()                                              # eager work between the replays
+        torch.cuda.synchronize()
+    ctx.poll_error()
+    ctx.close()
