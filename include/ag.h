@@ -136,6 +136,18 @@ ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const vo
                           float scale, const ag_kv_cache *cache, void *out);
 
 /*
+ * The same attention with a window of recent tokens that stay visible whatever their flag (Table 5, the
+ * "keep recent tokens" settings): the visible keys of row j are
+ *   { t < j : flags[b,g,t] != 0 }  plus  { t : j - n_recent < t <= j }.
+ * n_recent = 1 is ag_prefill_attn (only the diagonal); 1 <= n_recent <= 64, else AG_EINVAL.  Arguments, layouts
+ * and the meaning of `cache` are those of ag_prefill_attn; the evicted tokens inside the window are read from
+ * k, v (they are not in the cache).
+ */
+ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                                 const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype,
+                                 float scale, const ag_kv_cache *cache, int n_recent, void *out);
+
+/*
  * One decoding step (Sec. 3.1 decoding stage; the gate is not run during decoding, Sec. 3.4).
  * For every (b, query head i): keys = cache rows of unit (b, g) followed by k_new[b,g]; same for values;
  * out[b,i,:] = softmax-weighted sum (the new token always attends to itself, Eq. 5 diagonal; an empty cache

@@ -262,7 +262,14 @@ ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void
 ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
                           const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, float scale,
                           const ag_kv_cache *cache, void *out) {
+  return ag_prefill_attn_recent(ctx, hip_stream, q, k, v, flags, B, L, Hq, Hkv, D, dtype, scale, cache, 1, out);
+}
+
+ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                                 const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype,
+                                 float scale, const ag_kv_cache *cache, int n_recent, void *out) {
   if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(n_recent >= 1 && n_recent <= 64, AG_EINVAL, "ag_prefill_attn: n_recent = %d outside [1, 64]", n_recent);
   AG_REQUIRE(q && k && v && flags && out, AG_EINVAL, "ag_prefill_attn: null pointer");
   AG_REQUIRE(B > 0 && L > 0 && Hq > 0 && Hkv > 0 && D > 0, AG_EINVAL, "ag_prefill_attn: sizes must be positive");
   AG_REQUIRE(Hq % Hkv == 0, AG_EINVAL, "ag_prefill_attn: Hq %% Hkv != 0");
@@ -314,8 +321,8 @@ ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const vo
     AG_HIP(ag_launch_slab_offsets(s, wro, units, L));
     AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(D * esz), 0, wk, wv, widx, wro, wlen));
   }
-  AG_HIP(ag_launch_prefill(ctx, s, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, kc, vc, row_off, out, plan,
-                           part));
+  AG_HIP(ag_launch_prefill(ctx, s, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, n_recent, kc, vc, row_off,
+                           out, plan, part));
   return AG_OK;
 }
 

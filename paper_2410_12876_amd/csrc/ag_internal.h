@@ -93,16 +93,16 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
 
 hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const void *k, const void *v,
                              const uint64_t *words, const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D,
-                             ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
-                             void *out, const ag_pf_plan &plan, float *part);
+                             ag_dtype dt, float scale, int n_recent, const void *kc, const void *vc,
+                             const int64_t *row_off, void *out, const ag_pf_plan &plan, float *part);
 
 // bf16, D = 128: the tuned kernel of ag_prefill_d128.hip (qscale = scale * log2 e).  ag_prefill_d128_plan carves
 // the plan's buffers and the partial-state buffer out of the workspace (plan.n_split == 1: no key split).
 void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &ws, ag_pf_plan *plan, float **part);
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
-                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, const void *kc,
-                                  const void *vc, const int64_t *row_off, void *out, const ag_pf_plan &plan,
-                                  float *part);
+                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
+                                  const void *kc, const void *vc, const int64_t *row_off, void *out,
+                                  const ag_pf_plan &plan, float *part);
 
 hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw,
-    float qscale, uint16_t *__restrict__ out) {
+    float qscale, int n_recent, uint16_t *__restrict__ out) {
   constexpr int QW = 4 / GB;       // query sub-tiles per workgroup
   constexpr int BM = 32 * QW;      // queries per workgroup
   constexpr int KS = D / 16;       // MFMA k-steps over the head dimension
@@ -110,16 +110,20 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
   const uint16_t *Kc = kc + (size_t)row_off[u] * D;
   const uint16_t *Vc = vc + (size_t)row_off[u] * D;
 
-  for (int c0 = 0; c0 < cnt_blk; c0 += kBN) {
+  // One 64-key tile: rows [r0, r0 + 64) of src_k / src_v (rows outside [0, r_end) read as zero).  Compacted tiles
+  // (band == false) hide keys at or past the query's boundary cnt_q.  Band tiles (band == true) come from the
+  // uncompacted K/V and show only the evicted tokens (keep bit clear in bword) among the n_recent - 1 tokens just
+  // before the query: the kept ones are already among the compacted rows (Table 5, recent-token settings).
+  auto tile = [&](const uint16_t *src_k, const uint16_t *src_v, int r0, int r_end, bool band, uint64_t bword) {
     __syncthreads();  // previous tile fully consumed
-    // ---- stage K tile (row-major) and V tile (transposed) in LDS; rows past the unit's length are zero ----
+    // ---- stage K tile (row-major) and V tile (transposed) in LDS ----
     constexpr int CPR = D / 8;  // 16-byte chunks per row
     for (int ch = tid; ch < kBN * CPR; ch += 256) {
       const int r = ch / CPR, sg = ch - r * CPR;
       uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (c0 + r < len_u) {
-        kk = *reinterpret_cast<const uint4 *>(Kc + (size_t)(c0 + r) * D + sg * 8);
-        vv = *reinterpret_cast<const uint4 *>(Vc + (size_t)(c0 + r) * D + sg * 8);
+      if (r0 + r < r_end) {
+        kk = *reinterpret_cast<const uint4 *>(src_k + (size_t)(r0 + r) * D + sg * 8);
+        vv = *reinterpret_cast<const uint4 *>(src_v + (size_t)(r0 + r) * D + sg * 8);
       }
       *reinterpret_cast<uint4 *>(&Ks[r * KSTR + sg * 8]) = kk;
       const uint32_t va[4] = {vv.x, vv.y, vv.z, vv.w};
@@ -130,7 +134,8 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
       }
     }
     __syncthreads();
-    if (c0 >= cnt_wave_hi) continue;  // nothing visible to this wave in the tile (wave-uniform)
+    // nothing visible to this wave in the tile (wave-uniform)?
+    if (band ? (j0 >= L || r0 > j0 + 30 || r0 + kBN - 1 < j0 - (n_recent - 1)) : (r0 >= cnt_wave_hi)) return;
 
     // ---- S^T = K_tile . Q^T ----
     f32x16 acc_s[2];
@@ -145,13 +150,25 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
                                                              __builtin_bit_cast(bf16x8, qf[ks]), acc_s[sub], 0, 0, 0);
       }
     }
-    // acc_s[sub][r]: key = c0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col
-    if (c0 + kBN > cnt_wave_lo) {  // tile crosses some query's boundary: mask keys >= cnt_q
+    // acc_s[sub][r]: key = r0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col
+    if (band) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const uint32_t wsub = (uint32_t)(bword >> (32 * sub + 4 * hb));  // keep bits of this lane's 16 keys
+        const int dl = jq - 1 - r0 - 32 * sub - 4 * hb;                  // (query - 1) - key for c = 0
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int c = 8 * (r >> 2) + (r & 3);
+          const bool in_window = (unsigned)(dl - c) < (unsigned)(n_recent - 1);  // query - n_recent < key < query
+          if (!in_window || ((wsub >> c) & 1u)) acc_s[sub][r] = -INFINITY;
+        }
+      }
+    } else if (r0 + kBN > cnt_wave_lo) {  // tile crosses some query's boundary: mask keys >= cnt_q
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int key = c0 + 32 * sub + 8 * (r >> 2) + 4 * hb + (r & 3);
+          const int key = r0 + 32 * sub + 8 * (r >> 2) + 4 * hb + (r & 3);
           if (key >= cnt_q) acc_s[sub][r] = -INFINITY;
         }
     }
@@ -199,6 +216,13 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
           acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                               __builtin_bit_cast(bf16x8, pf[sub][sl]), acc_o[dt], 0, 0, 0);
         }
+  };
+  for (int c0 = 0; c0 < cnt_blk; c0 += kBN) tile(Kc, Vc, c0, len_u, false, 0);
+  if (n_recent > 1) {  // workgroup-uniform: band tiles that can hold a key of one of the workgroup's queries
+    const int jb = min(qtile * BM + BM - 1, L - 1);
+    const int klo = max(0, qtile * BM - (n_recent - 1)), khi = jb - 1;
+    for (int bt = klo >> 6; bt <= (khi >> 6) && khi >= klo; ++bt)
+      tile(k + (size_t)u * L * D, v + (size_t)u * L * D, bt * kBN, L, true, wu[bt]);
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -225,7 +249,8 @@ __global__ __launch_bounds__(256) void ag_prefill_f32_kernel(const float *__rest
                                                              const int32_t *__restrict__ blk_off,
                                                              const float *__restrict__ kc, const float *__restrict__ vc,
                                                              const int64_t *__restrict__ row_off, int L, int Hq,
-                                                             int Hkv, int nw, float qscale, float *__restrict__ out) {
+                                                             int Hkv, int nw, float qscale, int n_recent,
+                                                             float *__restrict__ out) {
   constexpr int DPL = (D + 63) / 64;  // output columns per lane
   __shared__ float qs[4][D];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -252,6 +277,23 @@ __global__ __launch_bounds__(256) void ag_prefill_f32_kernel(const float *__rest
   float m = s_self, l = 1.f, o[DPL];
 #pragma unroll
   for (int e = 0; e < DPL; ++e) o[e] = lane + 64 * e < D ? vself[lane + 64 * e] : 0.f;
+
+  // recent-token band (Table 5): evicted tokens among the n_recent - 1 just before the query stay visible; the
+  // kept ones are among the cache rows already.  Wave-uniform loop, one key at a time.
+  for (int i = 1; i < n_recent && j - i >= 0; ++i) {
+    const int t = j - i;
+    if ((words[(size_t)u * nw + (t >> 6)] >> (t & 63)) & 1ull) continue;
+    const float *kr = k + ((size_t)u * L + t) * D, *vr = v + ((size_t)u * L + t) * D;
+    float s = 0.f;
+    for (int d = 0; d < D; ++d) s = fmaf(qs[wave][d], kr[d], s);
+    const float mn = fmaxf(m, s);
+    const float alpha = exp2f(m - mn), p = exp2f(s - mn);
+    m = mn;
+    l = l * alpha + p;
+#pragma unroll
+    for (int e = 0; e < DPL; ++e)
+      if (lane + 64 * e < D) o[e] = fmaf(p, vr[lane + 64 * e], o[e] * alpha);
+  }
 
   for (int c0 = 0; c0 < cnt; c0 += 64) {
     const int c = c0 + lane;
@@ -296,15 +338,15 @@ bool ag_prefill_supported(ag_dtype dt, int D, int G) {
 
 hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const void *k, const void *v,
                              const uint64_t *words, const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D,
-                             ag_dtype dt, float scale, const void *kc, const void *vc, const int64_t *row_off,
-                             void *out, const ag_pf_plan &plan, float *part) {
+                             ag_dtype dt, float scale, int n_recent, const void *kc, const void *vc,
+                             const int64_t *row_off, void *out, const ag_pf_plan &plan, float *part) {
   const int nw = ag_nwords(L);
   ag_tick(ctx, AG_K_PREFILL, s);
   const int G = Hq / Hkv;
   const float qscale = scale * kLog2e;
   if (dt == AG_BF16 && D == 128) {
-    const hipError_t e = ag_launch_prefill_d128(s, q, k, v, words, blk_off, B, L, Hq, Hkv, qscale, kc, vc, row_off, out,
-                                                plan, part);
+    const hipError_t e = ag_launch_prefill_d128(s, q, k, v, words, blk_off, B, L, Hq, Hkv, qscale, n_recent, kc, vc,
+                                                row_off, out, plan, part);
     ag_tock(ctx, AG_K_PREFILL, s);
     return e;
   }
@@ -315,19 +357,15 @@ hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const vo
 #define AG_PF(DD, GG)                                                                                             \
   hipLaunchKernelGGL((ag_prefill_mfma_kernel<DD, GG>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k, \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
-                     Hkv, nw, qscale, (uint16_t *)out)
-    if (D == 128) {
-      if (GB == 1) AG_PF(128, 1); else if (GB == 2) AG_PF(128, 2); else AG_PF(128, 4);
-    } else {
-      if (GB == 1) AG_PF(64, 1); else if (GB == 2) AG_PF(64, 2); else AG_PF(64, 4);
-    }
+                     Hkv, nw, qscale, n_recent, (uint16_t *)out)
+    if (GB == 1) AG_PF(64, 1); else if (GB == 2) AG_PF(64, 2); else AG_PF(64, 4);  // D = 128 took the tuned kernel
 #undef AG_PF
   } else {
     const dim3 grid((L + 3) / 4, B * Hq), block(256);
 #define AG_PF32(DD)                                                                                              \
   hipLaunchKernelGGL((ag_prefill_f32_kernel<DD>), grid, block, 0, s, (const float *)q, (const float *)k,           \
                      (const float *)v, words, blk_off, (const float *)kc, (const float *)vc, row_off, L, Hq, Hkv, nw, \
-                     qscale, (float *)out)
+                     qscale, n_recent, (float *)out)
     if (D == 32) AG_PF32(32); else if (D == 64) AG_PF32(64); else if (D == 128) AG_PF32(128); else AG_PF32(256);
 #undef AG_PF32
   }

@@ -75,13 +75,17 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 // GB = query heads of one KV group per workgroup (one per wave).  n_split = chunks per item in the grid,
 // chunk_tiles_dev = key tiles per chunk (device value, NULL without a split); part = partial states
 // [item][chunk][4 waves][66][64] fp32 and tickets = per-item arrival counters (n_split > 1).
-template <int GB>
+// BAND = the recent-token variant (Table 5): the evicted tokens among the n_recent - 1 tokens just before a query
+// stay visible to it.  They are read from the uncompacted K/V as up to three extra 64-key "band" tiles that run
+// through the same pipeline ahead of the compacted tiles of chunk 0, with their own mask.
+template <int GB, bool BAND>
 __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw, int n_hy,
-    int n_split, const int32_t *__restrict__ chunk_tiles_dev, float qscale, const int32_t *__restrict__ order,
-    uint16_t *__restrict__ out, float *__restrict__ part, int32_t *__restrict__ tickets) {
+    int n_split, const int32_t *__restrict__ chunk_tiles_dev, float qscale, int n_recent,
+    const int32_t *__restrict__ order, uint16_t *__restrict__ out, float *__restrict__ part,
+    int32_t *__restrict__ tickets) {
   constexpr int QW = 4 / GB;   // query sub-tiles per workgroup
   constexpr int BM = 32 * QW;  // queries per workgroup
   constexpr int KS = D / 16;   // k-steps of S^T
@@ -140,8 +144,23 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     AG_TRACE_END(0, 1)
     return;
   }
-  const int n_steps = max(0, min(n_tiles - tile0, chunk_tiles));
   const int n_chunks = max(1, (n_tiles + chunk_tiles - 1) / chunk_tiles);
+  // band tiles (chunk 0 only): 64-aligned tiles of original token positions that can hold a key of this
+  // workgroup's queries, i.e. positions [first query - (n_recent - 1), last query - 1]
+  int n_band = 0, band_t0 = 0;
+  uint64_t bw0 = 0, bw1 = 0, bw2 = 0;  // keep masks of the band tiles
+  if (BAND && chunk == 0) {
+    const int klo = max(0, qtile * BM - (n_recent - 1)), khi = jb - 1;
+    if (khi >= klo) {
+      band_t0 = klo >> 6;
+      n_band = (khi >> 6) - band_t0 + 1;  // <= 3 because n_recent <= 64 and BM <= 128
+      bw0 = wu[band_t0];
+      if (n_band > 1) bw1 = wu[band_t0 + 1];
+      if (n_band > 2) bw2 = wu[band_t0 + 2];
+    }
+  }
+  // steps of this workgroup: the band tiles first, then its chunk of compacted tiles
+  const int n_steps = n_band + max(0, min(n_tiles - tile0, chunk_tiles));
 
   const size_t qrow = ((size_t)(b * Hq + head) * L + jq) * D;
   const size_t kvrow = ((size_t)u * L + jq) * D;
@@ -157,6 +176,11 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   // (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
   const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kc, 0, len_u * kRowB, 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vc, 0, len_u * kRowB, 0x00020000);
+  // the unit's uncompacted rows (band tiles); rows past the prompt's end arrive as zeros and are masked
+  const __amdgpu_buffer_rsrc_t kb_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void *)(k + (size_t)u * L * D), 0, BAND ? L * kRowB : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vb_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void *)(v + (size_t)u * L * D), 0, BAND ? L * kRowB : 0, 0x00020000);
   const int ld_r = lane >> 4;
   int ld_off[4];
 #pragma unroll
@@ -164,21 +188,25 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     ld_off[i] = (16 * w4 + 4 * i + ld_r) * kRowB + (((lane & 15) ^ ((ld_r << 2) | i)) << 4);  // chunk (lane%16)^swz(r)
   const uint32_t ld_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + w4 * 16 * kRowB;
   auto issue_k = [&](int i_step) {  // K of the tile of step i_step -> K buffer i_step & 1
-    const int soff = (tile0 + i_step) * kTileB;
+    const bool bnd = BAND && i_step < n_band;
+    const int soff = (bnd ? band_t0 + i_step : tile0 + i_step - n_band) * kTileB;
+    const __amdgpu_buffer_rsrc_t rsrc = bnd ? kb_rsrc : k_rsrc;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t dk = ld_base + (i_step & 1) * kTileB + i * 4 * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                   :: "s"(dk), "v"(ld_off[i]), "s"(k_rsrc), "s"(soff) : "memory");
+                   :: "s"(dk), "v"(ld_off[i]), "s"(rsrc), "s"(soff) : "memory");
     }
   };
   auto issue_v = [&](int i_step) {
-    const int soff = (tile0 + i_step) * kTileB;
+    const bool bnd = BAND && i_step < n_band;
+    const int soff = (bnd ? band_t0 + i_step : tile0 + i_step - n_band) * kTileB;
+    const __amdgpu_buffer_rsrc_t rsrc = bnd ? vb_rsrc : v_rsrc;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t dv = ld_base + 2 * kTileB + (i_step & 1) * kTileB + i * 4 * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                   :: "s"(dv), "v"(ld_off[i]), "s"(v_rsrc), "s"(soff) : "memory");
+                   :: "s"(dv), "v"(ld_off[i]), "s"(rsrc), "s"(soff) : "memory");
     }
   };
   if (n_steps > 0) { issue_k(0); issue_v(0); }
@@ -322,6 +350,33 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
         }
     }
   };
+  // band tile of step i: key position t = 64 (band_t0 + i) + kk is visible to query jq iff it lies among the
+  // n_recent - 1 positions before jq and its keep bit is clear (kept tokens are among the compacted rows)
+  auto band_mask = [&](int i, f32x16 (&acc)[2]) {
+    const int r0 = (band_t0 + i) * kBN;
+    const uint64_t bword = i == 0 ? bw0 : (i == 1 ? bw1 : bw2);
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      // this lane's keys of the sub-tile are 32 sub + 4 hb + c with c = 8 (r/4) + r%4: one 32-bit slice of the keep
+      // mask and one distance, then compile-time shifts per element
+      const uint32_t wsub = (uint32_t)(bword >> (32 * sub + 4 * hb));
+      const int dl = jq - 1 - r0 - 32 * sub - 4 * hb;  // (query - 1) - key for c = 0
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int c = 8 * (r >> 2) + (r & 3);
+        const bool in_window = (unsigned)(dl - c) < (unsigned)(n_recent - 1);  // query - n_recent < key < query
+        if (!in_window || ((wsub >> c) & 1u)) acc[sub][r] = -INFINITY;
+      }
+    }
+  };
+  // does step i hold a key that some query of this wave may see?  (wave-uniform)
+  auto vis = [&](int i) -> bool {
+    if (BAND && i < n_band) {
+      const int r0 = (band_t0 + i) * kBN;
+      return j0 < L && r0 <= j0 + 30 && r0 + kBN - 1 >= j0 - (n_recent - 1);
+    }
+    return (tile0 + i - n_band) * kBN < cnt_wave_hi;
+  };
   auto pv_tile = [&](int i_step) {  // O^T += V(tile)^T . P^T, after the pending rescale
     if (any_raise) {
 #pragma unroll
@@ -358,11 +413,15 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     __syncthreads();                                  // ... and everyone's; step i-1 is fully consumed
     if (i + 2 < n_steps) issue_k(i + 2);
     if (i + 1 < n_steps) issue_v(i + 1);
-    const int c0 = (tile0 + i) * kBN;
-    const bool vis_cur = c0 < cnt_wave_hi;                                       // wave-uniform
-    const bool vis_nxt = i + 1 < n_steps && c0 + kBN < cnt_wave_hi;              // wave-uniform
-    if (vis_cur) mask_tile(c0, cur);
-    if (vis_nxt) {
+    const int c0 = (tile0 + i - n_band) * kBN;
+    const bool vis_cur = vis(i);                                                 // wave-uniform
+    const bool vis_nxt = i + 1 < n_steps && vis(i + 1);                          // wave-uniform
+    if (vis_cur) {
+      if (BAND && i < n_band) band_mask(i, cur); else mask_tile(c0, cur);
+    }
+    if (BAND && vis_nxt && !vis_cur) {
+      s_tile(i + 1, nxt);   // band tiles are not all visible to a wave: the next tile may be the first it sees
+    } else if (vis_nxt) {
       s_tile(i + 1, nxt);   // MFMA stream ...
       softmax_tile(cur);    // ... and an independent VALU stream; the groups below interleave them:
       // 4 K-fragment reads ahead, then per MFMA one more read and a slice of the softmax arithmetic
@@ -382,7 +441,7 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   if (n_steps > 0) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (tile0 * kBN < cnt_wave_hi) s_tile(0, acc_a);
+    if (vis(0)) s_tile(0, acc_a);
   }
   for (int i = 0; i < n_steps; i += 2) {
     step(i, acc_a, acc_b);
@@ -418,20 +477,23 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     for (int c = 0; c < n_chunks; ++c)
       if (c != chunk) m = fmaxf(m, peek(&st[c * cstride + 64 * 64]));
     const float f_own = __builtin_amdgcn_exp2f(m_run - m);
-    l_run *= f_own;
+    l_run = __fmul_rn(l_run, f_own);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc_o[dt][r] *= f_own;
+      for (int r = 0; r < 16; ++r) acc_o[dt][r] = __fmul_rn(acc_o[dt][r], f_own);
     for (int c = 0; c < n_chunks; ++c) {
       if (c == chunk) continue;
       const float *sc = st + c * cstride;
       const float f = __builtin_amdgcn_exp2f(peek(&sc[64 * 64]) - m);
-      l_run = fmaf(peek(&sc[65 * 64]), f, l_run);
+      // rounded product + rounded product (no fused multiply-add): the sum of two chunks is then the same
+      // bit pattern whichever of them arrives last and does the merge
+      l_run = __fadd_rn(__fmul_rn(peek(&sc[65 * 64]), f), l_run);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[dt][r] = fmaf(peek(&sc[(16 * dt + r) * 64]), f, acc_o[dt][r]);
+        for (int r = 0; r < 16; ++r)
+          acc_o[dt][r] = __fadd_rn(__fmul_rn(peek(&sc[(16 * dt + r) * 64]), f), acc_o[dt][r]);
     }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -465,6 +527,8 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
   plan->max_tiles = (L + kBN - 1) / kBN;
   plan->slots = 2 * num_cu;
   plan->n_split = 1;
+  // (at most two chunks: the merge adds two rounded products, which is the same bit pattern in either order; more
+  // chunks would need a fixed merge order to stay reproducible)
   if (items < (int64_t)8 * num_cu && plan->max_tiles > 16) plan->n_split = 2;
   *part = nullptr;
   if (plan->n_split > 1) {
@@ -484,21 +548,25 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
 }
 
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
-                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, const void *kc,
-                                  const void *vc, const int64_t *row_off, void *out, const ag_pf_plan &plan,
-                                  float *part) {
+                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
+                                  const void *kc, const void *vc, const int64_t *row_off, void *out,
+                                  const ag_pf_plan &plan, float *part) {
   (void)B;
   const int nw = ag_nwords(L);
   const int G = Hq / Hkv;
   const int GB = G >= 4 ? 4 : G;
   if ((int64_t)plan.n_items * plan.n_split > 0x7fffffff) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(plan.n_items * plan.n_split)), block(256);
-#define AG_PF(GG)                                                                                                   \
-  hipLaunchKernelGGL((ag_prefill_d128_kernel<GG>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k,        \
+#define AG_PF(GG, BB)                                                                                               \
+  hipLaunchKernelGGL((ag_prefill_d128_kernel<GG, BB>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k,    \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
-                     Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, plan.order, (uint16_t *)out, part,  \
-                     plan.tickets)
-  if (GB == 1) AG_PF(1); else if (GB == 2) AG_PF(2); else AG_PF(4);
+                     Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, n_recent, plan.order,               \
+                     (uint16_t *)out, part, plan.tickets)
+  if (n_recent > 1) {
+    if (GB == 1) AG_PF(1, true); else if (GB == 2) AG_PF(2, true); else AG_PF(4, true);
+  } else {
+    if (GB == 1) AG_PF(1, false); else if (GB == 2) AG_PF(2, false); else AG_PF(4, false);
+  }
 #undef AG_PF
   return hipGetLastError();
 }

@@ -263,3 +263,75 @@ def test_whole_step_replays_from_a_hip_graph():
         torch.cuda.synchronize()
     ctx.poll_error()
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------- recent-token window
+def _prefill_recent(q, k, v, flags, scale, n_recent, with_cache=True):
+    B, Hq, L, D = q.f32.shape
+    Hkv = k.f32.shape[1]
+    dt = ag.AG_BF16 if q.is_bf16 else ag.AG_F32
+    ctx = make_ctx(B, L, Hq, Hkv, D, dt)
+    dq, dk, dv, df = dev(q), dev(k), dev(v), dev(flags)
+    out = torch.empty_like(dq)
+    cache = None
+    if with_cache:
+        cache = new_cache(B, Hkv, D, dq.dtype, oracle.slab_row_off(B * Hkv, L))
+        ag.ag_compact_kv(ctx, dk, dv, df, 0, cache)
+    ag.ag_prefill_attn_recent(ctx, dq, dk, dv, df, scale, cache, n_recent, out)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    ctx.close()
+    return out
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,L,D,keep,n_recent,with_cache", [
+    ("f32", 1, 4, 4, 128, 64, 0.5, 5, True),
+    ("f32", 2, 4, 2, 77, 128, 0.3, 10, False),
+    ("bf16", 2, 4, 4, 300, 64, 0.4, 5, True),        # generic MFMA kernel
+    ("bf16", 1, 8, 2, 200, 64, 0.5, 10, True),       # ... with four query heads per workgroup
+    ("bf16", 2, 2, 2, 300, 128, 0.5, 5, True),       # tuned D = 128 kernel
+    ("bf16", 1, 4, 4, 257, 128, 0.3, 10, False),
+    ("bf16", 1, 8, 2, 333, 128, 0.5, 10, True),      # GQA, 32 queries per workgroup
+    ("bf16", 1, 4, 2, 500, 128, 0.2, 64, True),      # widest window, 64 queries per workgroup
+    ("bf16", 1, 2, 2, 3, 128, 0.5, 10, True),        # prompt shorter than the window
+    ("bf16", 1, 2, 2, 130, 128, 0.0, 5, True),       # nothing kept: plain sliding-window attention
+])
+def test_prefill_recent_window(dtype, B, Hq, Hkv, L, D, keep, n_recent, with_cache):
+    """Table 5's recent-token settings: keys within n_recent - 1 positions before the query stay visible."""
+    g = np.random.default_rng(100 + L + n_recent)
+    q, k, v = (W.store(g.standard_normal(s).astype(np.float32), dtype)
+               for s in ((B, Hq, L, D), (B, Hkv, L, D), (B, Hkv, L, D)))
+    flags = (g.random((B, Hkv, L)) < keep).astype(np.uint8)
+    scale = 1.0 / math.sqrt(D)
+    got = host_f32(_prefill_recent(q, k, v, flags, scale, n_recent, with_cache))
+    ref = oracle.prefill_attn(q.f32, k.f32, v.f32, flags, scale, n_recent=n_recent)
+    err, tol = attn_error(dtype, got, ref), attn_tolerance(dtype, ref)
+    assert np.isfinite(got).all() and err <= tol, "err %.3g > tol %.3g" % (err, tol)
+    # the window changes the result (the case would pass vacuously otherwise)
+    if keep < 1.0 and L > 2:
+        assert np.abs(ref - oracle.prefill_attn(q.f32, k.f32, v.f32, flags, scale)).max() > 1e-3
+
+
+def test_prefill_recent_window_full_size_and_window_of_one():
+    """Config-2-sized launch (key-chunk split, balanced head order) with a window of 10, on sampled rows; and a
+    window of 1 is ag_prefill_attn bit for bit."""
+    B, H, L, D = 1, 32, 4096, 128
+    g = np.random.default_rng(110)
+    q, k, v = (W.store(g.standard_normal((B, H, L, D)).astype(np.float32), "bf16") for _ in range(3))
+    flags = (g.random((B, H, L)) < np.linspace(0.2, 0.9, H)[None, :, None]).astype(np.uint8)
+    scale = 1.0 / math.sqrt(D)
+    out = _prefill_recent(q, k, v, flags, scale, 10)
+    rows = sample_rows(L, 111, 6)
+    ref = oracle.prefill_rows(q.f32, k.f32, v.f32, flags, scale, rows, n_recent=10)
+    got = host_f32(out)[:, :, rows, :]
+    assert attn_error("bf16", got, ref) <= attn_tolerance("bf16", ref) and attn_rms_error(got, ref) <= 5e-3
+    one = _prefill_recent(q, k, v, flags, scale, 1)
+    ctx = make_ctx(B, L, H, H, D, ag.AG_BF16)
+    dq, dk, dv, df = dev(q), dev(k), dev(v), dev(flags)
+    cache = new_cache(B, H, D, torch.bfloat16, oracle.slab_row_off(B * H, L))
+    ag.ag_compact_kv(ctx, dk, dv, df, 0, cache)
+    plain = torch.empty_like(dq)
+    ag.ag_prefill_attn(ctx, dq, dk, dv, df, scale, cache, plain)
+    torch.cuda.synchronize()
+    ctx.close()
+    assert torch.equal(one, plain)
