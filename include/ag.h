@@ -158,6 +158,31 @@ ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, c
 ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
                          const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache, void *out);
 
+/*
+ * Decoding with the recent-token window (Table 5, "keep recent tokens"): the tokens at the n_recent - 1 positions
+ * before the new one stay visible whatever their flag.  The evicted ones are not in the cache, so the last
+ * n_recent tokens of every unit live in a small ring, slot = position % n_recent (caller-owned device memory):
+ *   k, v   [B*Hkv, n_recent, D] in the cache's dtype;  flags uint8 [B*Hkv, n_recent] (keep flag of the token in
+ *   the slot);  pos int32 [B*Hkv, n_recent] (its position; a large negative number marks an empty slot).
+ * ag_recent_fill loads the ring with the last min(L, n_recent) prompt tokens (k, v [B, Hkv, L, D], flags
+ * [B, Hkv, L], first token at position pos0) and marks the other slots empty; call it once after prefilling.
+ * ag_decode_attn_recent is ag_decode_attn plus: every ring token t with pos - n_recent < t < pos and flag 0 is one
+ * more key/value (those with flag 1 are cache rows already); afterwards the new token (with its flag) takes slot
+ * pos % n_recent.  `pos` must advance by one per step.  ring == NULL is ag_decode_attn.  2 <= n_recent <= 64.
+ */
+typedef struct {
+  void *k, *v;
+  uint8_t *flags;
+  int32_t *pos;
+  int32_t n_recent;
+} ag_recent_ring;
+
+ag_status ag_recent_fill(ag_ctx *ctx, void *hip_stream, const void *k, const void *v, const uint8_t *flags, int B,
+                         int L, int Hkv, int D, ag_dtype dtype, int pos0, ag_recent_ring *ring);
+ag_status ag_decode_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                                const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache,
+                                ag_recent_ring *ring, void *out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,12 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
            "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
-           "ag_decode_attn"]
+           "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent"]
+
+
+class ag_recent_ring(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("flags", C.c_void_p), ("pos", C.c_void_p),
+                ("n_recent", C.c_int32)]
 
 
 class AgError(RuntimeError):
@@ -82,6 +87,11 @@ def load() -> C.CDLL:
                                            C.POINTER(ag_kv_cache), i32, vp]
     lib.ag_decode_attn.restype = C.c_int
     lib.ag_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache), vp]
+    lib.ag_recent_fill.restype = C.c_int
+    lib.ag_recent_fill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, C.POINTER(ag_recent_ring)]
+    lib.ag_decode_attn_recent.restype = C.c_int
+    lib.ag_decode_attn_recent.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache),
+                                          C.POINTER(ag_recent_ring), vp]
     _lib = lib
     return lib
 
@@ -225,3 +235,28 @@ def ag_decode_attn(ctx: Context, q, k_new, v_new, new_flags, pos: int, scale: fl
     Hq = q.shape[1]
     ctx._check(ctx._lib.ag_decode_attn(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k_new), _ptr(v_new),
                                        _ptr(new_flags), pos, Hq, scale, C.byref(cache.c), _ptr(out)))
+
+
+class RecentRing:
+    """The last n_recent tokens of every (batch, KV head) unit for the recent-token window; tensors are the
+    caller's: k, v [B*Hkv, n_recent, D], flags u8 [B*Hkv, n_recent], pos i32 [B*Hkv, n_recent]."""
+
+    def __init__(self, k, v, flags, pos, n_recent: int):
+        self.k, self.v, self.flags, self.pos, self.n_recent = k, v, flags, pos, n_recent
+        self.c = ag_recent_ring(_ptr(k), _ptr(v), _ptr(flags), _ptr(pos), n_recent)
+
+
+def ag_recent_fill(ctx: Context, k, v, flags, pos0: int, ring: RecentRing, stream=None) -> None:
+    """k, v [B, Hkv, L, D], flags u8 [B, Hkv, L]: the ring takes the last prompt tokens."""
+    B, Hkv, L, D = k.shape
+    ctx._check(ctx._lib.ag_recent_fill(ctx._h, _stream_ptr(stream), _ptr(k), _ptr(v), _ptr(flags), B, L, Hkv, D,
+                                       _dtype_code(k), pos0, C.byref(ring.c)))
+
+
+def ag_decode_attn_recent(ctx: Context, q, k_new, v_new, new_flags, pos: int, scale: float, cache: KVCache,
+                          ring: Optional[RecentRing], out, stream=None) -> None:
+    """ag_decode_attn with the evicted tokens of the ring's window visible; the ring then takes the new token."""
+    Hq = q.shape[1]
+    ctx._check(ctx._lib.ag_decode_attn_recent(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                              _ptr(new_flags), pos, Hq, scale, C.byref(cache.c),
+                                              C.byref(ring.c) if ring is not None else None, _ptr(out)))

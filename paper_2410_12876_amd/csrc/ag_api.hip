@@ -326,12 +326,48 @@ ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, c
   return AG_OK;
 }
 
+namespace {
+ag_status check_ring(ag_ctx *ctx, const ag_recent_ring *r) {
+  AG_REQUIRE(r->k && r->v && r->flags && r->pos, AG_EINVAL, "ring: null pointer");
+  AG_REQUIRE(r->n_recent >= 2 && r->n_recent <= 64, AG_EINVAL, "ring: n_recent = %d outside [2, 64]", r->n_recent);
+  return AG_OK;
+}
+ag_ring_dev ring_dev(const ag_recent_ring *r) {
+  return r ? ag_ring_dev{r->k, r->v, r->flags, r->pos, r->n_recent} : ag_ring_dev{nullptr, nullptr, nullptr, nullptr, 0};
+}
+}  // namespace
+
+ag_status ag_recent_fill(ag_ctx *ctx, void *hip_stream, const void *k, const void *v, const uint8_t *flags, int B,
+                         int L, int Hkv, int D, ag_dtype dtype, int pos0, ag_recent_ring *ring) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(k && v && flags && ring, AG_EINVAL, "ag_recent_fill: null pointer");
+  AG_REQUIRE(B > 0 && L > 0 && Hkv > 0 && D > 0 && pos0 >= 0, AG_EINVAL, "ag_recent_fill: bad sizes");
+  AG_REQUIRE(dtype_ok(dtype), AG_EINVAL, "ag_recent_fill: unknown dtype %d", (int)dtype);
+  ag_status st = check_ring(ctx, ring);
+  if (st != AG_OK) return st;
+  st = need_device(ctx);
+  if (st != AG_OK) return st;
+  AG_HIP(ag_launch_ring_fill((hipStream_t)hip_stream, k, v, flags, B * Hkv, L, D, dtype, pos0, ring_dev(ring)));
+  return AG_OK;
+}
+
 ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
                          const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache, void *out) {
+  return ag_decode_attn_recent(ctx, hip_stream, q, k_new, v_new, new_flags, pos, Hq, scale, cache, nullptr, out);
+}
+
+ag_status ag_decode_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                                const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache,
+                                ag_recent_ring *ring, void *out) {
   if (!ctx) return AG_EINVAL;
   AG_REQUIRE(q && k_new && v_new && cache && out, AG_EINVAL, "ag_decode_attn: null pointer");
   ag_status st = check_cache(ctx, cache);
   if (st != AG_OK) return st;
+  if (ring) {
+    st = check_ring(ctx, ring);
+    if (st != AG_OK) return st;
+    AG_REQUIRE(pos >= 0, AG_EINVAL, "ag_decode_attn: pos must not be negative with a recent-token ring");
+  }
   AG_REQUIRE(Hq > 0 && Hq % cache->Hkv == 0, AG_EINVAL, "ag_decode_attn: Hq must be a positive multiple of Hkv");
   AG_REQUIRE(scale > 0.f && isfinite(scale), AG_EINVAL, "ag_decode_attn: scale must be positive and finite");
   const int G = Hq / cache->Hkv, units = cache->B * cache->Hkv;
@@ -344,7 +380,7 @@ ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const voi
   ws_cursor ws = cursor(ctx);
   hipError_t e = ag_launch_decode(ctx, (hipStream_t)hip_stream, q, k_new, v_new, new_flags, pos, cache->B, Hq, cache->Hkv,
                                   cache->D, cache->dtype, scale, cache->k, cache->v, cache->idx, cache->row_off,
-                                  cache->len, cache->total_rows, out, ws);
+                                  cache->len, cache->total_rows, out, ws, ring_dev(ring));
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_decode_attn: workspace too small (need %zu)", ws.off);
   AG_HIP(e);
   return AG_OK;

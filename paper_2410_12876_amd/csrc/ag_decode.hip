@@ -242,7 +242,7 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
                                                             T *__restrict__ vc, int32_t *__restrict__ idx,
                                                             const int64_t *__restrict__ row_off,
                                                             int32_t *__restrict__ len, T *__restrict__ out,
-                                                            int32_t *__restrict__ d_err) {
+                                                            int32_t *__restrict__ d_err, ag_ring_dev ring) {
   __shared__ float red[D / 64 > 0 ? D / 64 : 1];
   const int G = Hq / Hkv;
   const int bi = blockIdx.x;  // b * Hq + i
@@ -267,6 +267,30 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
   const int i0 = item_off[u], i1 = item_off[u + 1];
   const int lane = d & 63;
   float M = s_self, L = 1.f, A = vn;  // state so far: the new token alone, relative to M
+  // recent-token ring (Table 5): an evicted token among the n_recent - 1 positions before `pos` is still visible
+  // (the kept ones are cache rows already).  Slot contents are block-uniform, so the branches are too.
+  if (ring.k) {
+    const T *rk = static_cast<const T *>(ring.k), *rv = static_cast<const T *>(ring.v);
+    const float qd = widen1(q[(size_t)bi * D + d]) * qscale;
+    for (int w = 0; w < ring.n; ++w) {
+      const size_t slot = (size_t)u * ring.n + w;
+      const int p = ring.pos[slot];
+      if (!(p < pos && p > pos - ring.n) || ring.flags[slot] != 0) continue;
+      float part_r = qd * widen1(rk[slot * D + d]);
+      for (int o = 32; o > 0; o >>= 1) part_r += __shfl_xor(part_r, o, 64);
+      __syncthreads();  // red[] of the previous reduction is consumed
+      if ((d & 63) == 0) red[d >> 6] = part_r;
+      __syncthreads();
+      float sr = 0.f;
+#pragma unroll
+      for (int x = 0; x < (D + 63) / 64; ++x) sr += red[x];
+      const float M_new = fmaxf(M, sr);
+      const float keep = exp2f(M - M_new), pr = exp2f(sr - M_new);
+      M = M_new;
+      L = L * keep + pr;
+      A = fmaf(pr, widen1(rv[slot * D + d]), A * keep);
+    }
+  }
   for (int base = i0; base < i1; base += 64) {
     const int n = min(64, i1 - base);
     const size_t pr = (size_t)(base + lane) * G + gg;
@@ -310,6 +334,45 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
       atomicOr(d_err, 1);
     }
   }
+  // The new token takes the ring slot pos % n_recent.  That slot held position pos - n_recent, which no query
+  // head of this step can see any more, and a reader that races with the write skips the slot whether it finds
+  // the old position (out of the window) or the new one (not before pos).
+  if (ring.k && gg == 0) {
+    const size_t slot = (size_t)u * ring.n + (size_t)(pos % ring.n);
+    static_cast<T *>(ring.k)[slot * D + d] = k_new[(size_t)u * D + d];
+    static_cast<T *>(ring.v)[slot * D + d] = v_new[(size_t)u * D + d];
+    if (d == 0) {
+      ring.flags[slot] = (new_flags == nullptr || new_flags[u] != 0) ? 1 : 0;
+      ring.pos[slot] = pos;
+    }
+  }
+}
+
+// After prefilling: the ring takes the last min(L, n_recent) prompt tokens of every unit (kept or not); the other
+// slots are marked empty.  One workgroup per unit, one wave per token slot in turn.
+template <typename T>
+__global__ __launch_bounds__(256) void ag_ring_fill_kernel(const T *__restrict__ k, const T *__restrict__ v,
+                                                           const uint8_t *__restrict__ flags, int L, int D, int pos0,
+                                                           ag_ring_dev ring) {
+  const int u = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int w = wave; w < ring.n; w += 4) {
+    // slot w holds the position p with p % n == w among the last n positions before pos0 + L, if it is a prompt token
+    const int end = pos0 + L;                                   // first position after the prompt
+    const int p = end - 1 - ((end - 1 - w) % ring.n + ring.n) % ring.n;  // largest p < end with p % n == w
+    const int t = p - pos0;
+    const size_t slot = (size_t)u * ring.n + w;
+    if (t >= 0 && t < L && p >= 0) {
+      for (int d = lane; d < D; d += 64) {
+        static_cast<T *>(ring.k)[slot * D + d] = k[((size_t)u * L + t) * D + d];
+        static_cast<T *>(ring.v)[slot * D + d] = v[((size_t)u * L + t) * D + d];
+      }
+      if (lane == 0) { ring.flags[slot] = flags[(size_t)u * L + t] != 0; ring.pos[slot] = p; }
+    } else if (lane == 0) {
+      ring.flags[slot] = 1;
+      ring.pos[slot] = kRingEmpty;
+    }
+  }
 }
 
 int64_t max_items(int units, int64_t cache_rows) { return cache_rows / kChunk + units; }
@@ -317,7 +380,8 @@ int64_t max_items(int units, int64_t cache_rows) { return cache_rows / kChunk + 
 template <typename T, int D, int G>
 hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                     const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, float scale, void *kc, void *vc,
-                    int32_t *idx, const int64_t *row_off, int32_t *len, int64_t total_rows, void *out, ws_cursor &ws) {
+                    int32_t *idx, const int64_t *row_off, int32_t *len, int64_t total_rows, void *out, ws_cursor &ws,
+                    ag_ring_dev ring) {
   const int num_cu = ctx->num_cu;
   int32_t *d_err = ctx->d_err;
   const int U = B * Hkv;
@@ -345,7 +409,7 @@ hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new
   ag_tick(ctx, AG_K_DECODE_MERGE, s);
   hipLaunchKernelGGL((ag_decode_merge_kernel<T, D>), dim3(B * Hq), dim3(D), 0, s, (const T *)q, (const T *)k_new,
                      (const T *)v_new, new_flags, pos, Hq, Hkv, qscale, item_off, pm, pl, pacc, (T *)kc, (T *)vc, idx,
-                     row_off, len, (T *)out, d_err);
+                     row_off, len, (T *)out, d_err, ring);
   ag_tock(ctx, AG_K_DECODE_MERGE, s);
   return hipGetLastError();
 }
@@ -378,11 +442,11 @@ bool ag_decode_supported(ag_dtype dt, int D, int G, int units) {
 hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
                             float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
-                            int64_t total_rows, void *out, ws_cursor &ws) {
+                            int64_t total_rows, void *out, ws_cursor &ws, ag_ring_dev ring) {
   const int G = Hq / Hkv;
 #define AG_DEC(T, DD)                                                                                              \
   return launch_g<T, DD>(G, ctx, s, q, k_new, v_new, new_flags, pos, B, Hq, Hkv, scale, kc, vc, idx, row_off, len, \
-                         total_rows, out, ws)
+                         total_rows, out, ws, ring)
   if (dt == AG_BF16) {
     if (D == 64) AG_DEC(uint16_t, 64);
     if (D == 128) AG_DEC(uint16_t, 128);
@@ -392,4 +456,15 @@ hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const voi
   }
 #undef AG_DEC
   return hipErrorInvalidValue;
+}
+
+hipError_t ag_launch_ring_fill(hipStream_t s, const void *k, const void *v, const uint8_t *flags, int units, int L,
+                               int D, ag_dtype dt, int pos0, ag_ring_dev ring) {
+  if (dt == AG_BF16)
+    hipLaunchKernelGGL(ag_ring_fill_kernel<uint16_t>, dim3(units), dim3(256), 0, s, (const uint16_t *)k,
+                       (const uint16_t *)v, flags, L, D, pos0, ring);
+  else
+    hipLaunchKernelGGL(ag_ring_fill_kernel<float>, dim3(units), dim3(256), 0, s, (const float *)k, (const float *)v,
+                       flags, L, D, pos0, ring);
+  return hipGetLastError();
 }

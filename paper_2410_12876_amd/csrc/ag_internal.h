@@ -104,7 +104,20 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
                                   const void *kc, const void *vc, const int64_t *row_off, void *out,
                                   const ag_pf_plan &plan, float *part);
 
+// Device view of an ag_recent_ring (k == nullptr: no ring).  Slot w of unit u is element u * n + w.
+struct ag_ring_dev {
+  void *k, *v;      // [units, n, D]
+  uint8_t *flags;   // [units, n]
+  int32_t *pos;     // [units, n]
+  int n;            // slots per unit = n_recent
+};
+constexpr int32_t kRingEmpty = -(1 << 30);  // position stored in an empty ring slot
+
 hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new, const void *v_new,
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
                             float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
-                            int64_t total_rows, void *out, ws_cursor &ws);
+                            int64_t total_rows, void *out, ws_cursor &ws, ag_ring_dev ring);
+
+// Ring <- the last min(L, n) prompt tokens of every unit (k, v [units, L, D], flags [units, L]).
+hipError_t ag_launch_ring_fill(hipStream_t s, const void *k, const void *v, const uint8_t *flags, int units, int L,
+                               int D, ag_dtype dt, int pos0, ag_ring_dev ring);

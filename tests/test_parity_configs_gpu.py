@@ -335,3 +335,58 @@ def test_prefill_recent_window_full_size_and_window_of_one():
     torch.cuda.synchronize()
     ctx.close()
     assert torch.equal(one, plain)
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D,L,n_recent,keep", [("bf16", 2, 4, 2, 128, 50, 5, 0.4),
+                                                               ("f32", 1, 4, 4, 64, 37, 10, 0.5),
+                                                               ("bf16", 1, 8, 2, 128, 3, 10, 0.5),
+                                                               ("bf16", 2, 2, 2, 64, 200, 2, 0.1)])
+def test_decode_recent_window_against_the_prefill_definition(dtype, B, Hq, Hkv, D, L, n_recent, keep):
+    """Decoding with the ring of recent tokens: step s must equal row L + s of the windowed prefill definition over
+    the whole history (prompt + generated tokens with their flags), which the oracle computes from scratch each
+    step.  The cache itself evolves as without a window and is compared with the oracle's decode bit for bit."""
+    steps = 14
+    g = np.random.default_rng(120 + L)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    k_all = W.store(g.standard_normal((B, Hkv, L + steps, D)).astype(np.float32), dtype)
+    v_all = W.store(g.standard_normal((B, Hkv, L + steps, D)).astype(np.float32), dtype)
+    q_all = W.store(g.standard_normal((B, Hq, L + steps, D)).astype(np.float32), dtype)
+    f_all = (g.random((B, Hkv, L + steps)) < keep).astype(np.uint8)
+    scale = 1.0 / math.sqrt(D)
+    U = B * Hkv
+    ro = oracle.slab_row_off(U, L + steps)
+    ctx = make_ctx(B, L, Hq, Hkv, D, ag.AG_BF16 if dtype == "bf16" else ag.AG_F32, cache_rows=int(ro[-1]))
+    dk, dv, df = dev(k_all), dev(v_all), dev(f_all)
+    kp, vp, fp = dk[:, :, :L].contiguous(), dv[:, :, :L].contiguous(), df[:, :, :L].contiguous()
+    cache = new_cache(B, Hkv, D, tdt, ro)
+    ag.ag_compact_kv(ctx, kp, vp, fp, 0, cache)
+    ring = ag.RecentRing(torch.zeros(U, n_recent, D, dtype=tdt, device=DEV), torch.zeros(U, n_recent, D, dtype=tdt, device=DEV),
+                         torch.zeros(U, n_recent, dtype=torch.uint8, device=DEV),
+                         torch.zeros(U, n_recent, dtype=torch.int32, device=DEV), n_recent)
+    ag.ag_recent_fill(ctx, kp, vp, fp, 0, ring)
+    ref_cache, _ = oracle.compact_kv(k_all.f32[:, :, :L], v_all.f32[:, :, :L], f_all[:, :, :L], ro)
+    out = torch.empty(B, Hq, D, dtype=tdt, device=DEV)
+    dq = dev(q_all)
+    for s in range(steps):
+        p = L + s
+        ag.ag_decode_attn_recent(ctx, dq[:, :, p].contiguous(), dk[:, :, p].contiguous(), dv[:, :, p].contiguous(),
+                                 df[:, :, p].contiguous(), p, scale, cache, ring, out)
+        want = oracle.prefill_rows(q_all.f32[:, :, :p + 1], k_all.f32[:, :, :p + 1], v_all.f32[:, :, :p + 1],
+                                   f_all[:, :, :p + 1], scale, np.array([p]), n_recent=n_recent)[:, :, 0]
+        got = host_f32(out)
+        assert np.isfinite(got).all() and attn_error(dtype, got, want) <= attn_tolerance(dtype, want), "step %d" % s
+        oracle.decode_step(q_all.f32[:, :, p], k_all.f32[:, :, p], v_all.f32[:, :, p], f_all[:, :, p], p, ref_cache, scale)
+        assert np.array_equal(cache.len.cpu().numpy(), ref_cache.len)
+    gk, gi = host_f32(cache.k), cache.idx.cpu().numpy()
+    for u in range(U):
+        a, n = int(ro[u]), int(ref_cache.len[u])
+        assert np.array_equal(gk[a:a + n], ref_cache.k[a:a + n]) and np.array_equal(gi[a:a + n], ref_cache.idx[a:a + n])
+    # the ring now holds the last n_recent positions, each in slot position % n_recent, with its flag
+    end = L + steps
+    rp, rf, rk = ring.pos.cpu().numpy(), ring.flags.cpu().numpy(), host_f32(ring.k)
+    for p in range(max(0, end - n_recent), end):
+        assert (rp[:, p % n_recent] == p).all()
+        assert np.array_equal(rf[:, p % n_recent], f_all[:, :, p].reshape(U))
+        assert np.array_equal(rk[:, p % n_recent], k_all.f32[:, :, p].reshape(U, D))
+    ctx.poll_error()
+    ctx.close()
