@@ -70,6 +70,43 @@ def gate(feat, w, bias, tau: float, n_sink: int = 0):
     return logits, flags
 
 
+def _round_to(x: np.ndarray, store) -> np.ndarray:
+    """Value of x after being stored in `store` ("bf16": round to nearest even on the upper 16 bits of the fp32
+    pattern; "f32"; None: left in fp64)."""
+    if store is None:
+        return np.asarray(x, dtype=np.float64)
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    if store == "f32":
+        return x32.astype(np.float64)
+    assert store == "bf16"
+    b = x32.view(np.uint32)
+    b = (b + (np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+    return b.view(np.float32).astype(np.float64)
+
+
+def gate_mha(x, w_qkv, h_prime: int, d_prime: int, w_o, bias, tau: float, n_sink: int = 0, store=None):
+    """The main Attention-Gate module (Sec. 3.2, Eq. 3): MHA' over the hidden states, then the gate projection.
+
+    x [B,L,d]; w_qkv [d, 3*h'*d'] with column blocks (Q'|K'|V'), heads side by side inside a block;
+    w_o [h'*d', H_f]; bias [H_f].  Steps, in the paper's order:
+      Q',K',V' = X W'                                   (library matmul in fp64)
+      A_h      = causal softmax(Q'_h K'_h^T / sqrt d') V'_h    (prefill_attn with every flag set = no eviction)
+      logits   = concat_h(A_h) W^{O'} + bias;  flags by Eq. 4  (gate)
+    `store` names the dtype in which the module's tensors Q',K',V' and A are held between the steps ("bf16" for
+    a bf16 model, None = exact); the arithmetic itself stays fp64.
+    Returns (logits f64 [B,L,H_f], flags u8 [B,H_f,L])."""
+    x, w_qkv = np.asarray(_f32(x), dtype=np.float64), np.asarray(_f32(w_qkv), dtype=np.float64)
+    B, L, d = x.shape
+    hd = h_prime * d_prime
+    assert w_qkv.shape == (d, 3 * hd)
+    proj = _round_to(x.reshape(B * L, d) @ w_qkv, store).reshape(B, L, 3, h_prime, d_prime)
+    qp, kp, vp = (np.ascontiguousarray(proj[:, :, i].transpose(0, 2, 1, 3)) for i in range(3))  # [B,h',L,d']
+    ones = np.ones((B, h_prime, L), dtype=np.uint8)
+    a = prefill_attn(qp, kp, vp, ones, 1.0 / np.sqrt(d_prime))                                  # [B,h',L,d']
+    feat = _round_to(a, store).transpose(0, 2, 1, 3).reshape(B, L, hd)
+    return gate(feat, w_o, bias, tau, n_sink)
+
+
 def prefill_attn(q, k, v, flags, scale: float, n_recent: int = 1) -> np.ndarray:
     """q [B,Hq,L,D], k/v [B,Hkv,L,D], flags u8 [B,Hkv,L] -> out f64 [B,Hq,L,D]."""
     q, k, v = _f32(q), _f32(k), _f32(v)

@@ -133,6 +133,51 @@ def test_sampled_rows_vs_dense_mask_with_gqa(n_recent):
     assert oracle.prefill_rows(q, k, v, flags, 0.25, np.zeros(0, dtype=np.int32)).shape == (B, Hq, 0, D)
 
 
+# ------------------------------------------------------------------ main gate module (MHA' + projection)
+def test_gate_mha_vs_dense_write_up():
+    """Eq. 3 written out densely per head (explicit causal mask, numpy softmax) against oracle.gate_mha."""
+    B, L, d, hp, dp, H = 2, 19, 24, 3, 8, 5
+    x, wqkv, wo = rnd(50, B, L, d), rnd(51, d, 3 * hp * dp) * 0.3, rnd(52, hp * dp, H) * 0.4
+    bias = rnd(53, H) * 0.1
+    logits, flags = oracle.gate_mha(x, wqkv, hp, dp, wo, bias, 0.4, n_sink=1)
+    causal = np.tril(np.ones((L, L)))
+    for b in range(B):
+        proj = x[b].astype(np.float64) @ wqkv.astype(np.float64)            # [L, 3*hp*dp]
+        heads = []
+        for h in range(hp):
+            q, k, v = (proj[:, i * hp * dp + h * dp: i * hp * dp + (h + 1) * dp] for i in range(3))
+            heads.append(dense_masked_attention(q, k, v, causal, 1.0 / np.sqrt(dp)))
+        want = np.concatenate(heads, axis=1) @ wo.astype(np.float64) + bias
+        np.testing.assert_allclose(logits[b], want, rtol=1e-5, atol=1e-6)    # features pass through fp32 in gate()
+        f = (want > np.log(0.4 / 0.6)).T.astype(np.uint8)
+        f[:, 0] = 1
+        far = np.abs(want - np.log(0.4 / 0.6)).T > 1e-5
+        assert np.array_equal(flags[b][far], f[far])
+
+
+def test_gate_mha_closed_forms():
+    """W_q = 0 makes every causal softmax uniform, so A_j is the running mean of V'; L = 1 gives A = V'."""
+    B, L, d, hp, dp, H = 1, 11, 12, 2, 4, 3
+    x, wqkv, wo = rnd(54, B, L, d), rnd(55, d, 3 * hp * dp), rnd(56, hp * dp, H)
+    wqkv[:, :hp * dp] = 0.0
+    bias = np.zeros(H, np.float32)
+    logits, _ = oracle.gate_mha(x, wqkv, hp, dp, wo, bias, 0.5)
+    vprime = x[0].astype(np.float64) @ wqkv[:, 2 * hp * dp:].astype(np.float64)   # heads side by side = concat
+    run_mean = np.cumsum(vprime, axis=0) / np.arange(1, L + 1)[:, None]
+    np.testing.assert_allclose(logits[0], run_mean @ wo.astype(np.float64), rtol=1e-5, atol=1e-6)
+    one, _ = oracle.gate_mha(x[:, :1], rnd(57, d, 3 * hp * dp), hp, dp, wo, bias, 0.5)
+    v1 = x[0, :1].astype(np.float64) @ rnd(57, d, 3 * hp * dp)[:, 2 * hp * dp:].astype(np.float64)
+    np.testing.assert_allclose(one[0], v1 @ wo.astype(np.float64), rtol=1e-5, atol=1e-6)
+
+
+def test_gate_mha_storage_rounding_is_round_to_nearest_even_bf16():
+    vals = np.array([1.0, 1.00390625, 1.005859375, 1.01171875, -3.140625, 0.0], dtype=np.float64)
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-9 rounds up; 1 + 3*2^-8 is a tie -> 1 + 2^-6
+    got = oracle._round_to(vals, "bf16")
+    assert got.tolist() == [1.0, 1.0, 1.0078125, 1.015625, -3.140625, 0.0]
+    assert oracle._round_to(vals, None) is not None and np.array_equal(oracle._round_to(vals, None), vals)
+
+
 # ------------------------------------------------------------------ special cases -> library routines
 def test_all_kept_is_causal_sdpa():
     B, H, L, D = 2, 3, 50, 32
