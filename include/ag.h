@@ -114,6 +114,25 @@ ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtyp
                   uint8_t *flags_out);
 
 /*
+ * The paper's main gate (Sec. 3.2, Eq. 3): a small multi-head attention MHA' over the hidden states, then the
+ * gate's output projection and the threshold of Eq. 4.
+ *   Q', K', V' = x w_qkv     x [B, L, d_model]; w_qkv [d_model, 3 * h_prime * d_prime], columns ordered
+ *                            (Q' | K' | V'), inside each block head-major (head 0's d_prime columns first)
+ *   A          = per head, causal softmax(Q' K'^T / sqrt(d_prime)) V' over the whole prompt (nothing is
+ *                evicted inside the gate), stored in `dtype`
+ *   logits     = concat_heads(A) w_o + bias     w_o [h_prime * d_prime, H_f], bias fp32 [H_f]
+ *   flags      = logits > ln(tau / (1 - tau)); the first n_sink tokens forced to 1        (as ag_gate)
+ * logits_out fp32 [B, L, H_f] (NULL allowed), flags_out uint8 [B, H_f, L].  Built for bf16 with d_prime = 128
+ * (the paper's h' = 4, d'_k = 128), d_model % 64 == 0, H_f <= 32; anything else is AG_EUNSUPPORTED.  The
+ * intermediates live in the workspace; ag_gate_mha_workspace_bytes gives a sufficient size (0 for shapes that
+ * are not supported).
+ */
+size_t ag_gate_mha_workspace_bytes(int B, int L, int d_model, int h_prime, int d_prime, int H_f);
+ag_status ag_gate_mha(ag_ctx *ctx, void *hip_stream, const void *x, ag_dtype dtype, int B, int L, int d_model,
+                      const void *w_qkv, int h_prime, int d_prime, const void *w_o, const float *bias, int H_f,
+                      float tau, int n_sink, float *logits_out, uint8_t *flags_out);
+
+/*
  * KV-cache after prefilling (Sec. 3.3; Sec. 3.1 prefilling stage): stable stream compaction.
  * For each unit, rows t of k, v [B, Hkv, L, D] with flags[b,g,t] != 0 are copied, in increasing t, to the
  * unit's cache rows; idx gets pos0 + t and len the number of rows.  The result is unique, hence bit-exact.

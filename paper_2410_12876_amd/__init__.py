@@ -21,7 +21,7 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
            "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
-           "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent"]
+           "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
 
 
 class ag_recent_ring(C.Structure):
@@ -87,6 +87,10 @@ def load() -> C.CDLL:
                                            C.POINTER(ag_kv_cache), i32, vp]
     lib.ag_decode_attn.restype = C.c_int
     lib.ag_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache), vp]
+    lib.ag_gate_mha_workspace_bytes.restype = C.c_size_t
+    lib.ag_gate_mha_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.ag_gate_mha.restype = C.c_int
+    lib.ag_gate_mha.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, i32, i32, vp, vp, i32, f32, i32, vp, vp]
     lib.ag_recent_fill.restype = C.c_int
     lib.ag_recent_fill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, C.POINTER(ag_recent_ring)]
     lib.ag_decode_attn_recent.restype = C.c_int
@@ -260,3 +264,18 @@ def ag_decode_attn_recent(ctx: Context, q, k_new, v_new, new_flags, pos: int, sc
     ctx._check(ctx._lib.ag_decode_attn_recent(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k_new), _ptr(v_new),
                                               _ptr(new_flags), pos, Hq, scale, C.byref(cache.c),
                                               C.byref(ring.c) if ring is not None else None, _ptr(out)))
+
+
+def gate_mha_workspace_bytes(B: int, L: int, d_model: int, h_prime: int, d_prime: int, H_f: int) -> int:
+    return int(load().ag_gate_mha_workspace_bytes(B, L, d_model, h_prime, d_prime, H_f))
+
+
+def ag_gate_mha(ctx: Context, x, w_qkv, h_prime: int, d_prime: int, w_o, bias, tau: float, n_sink: int, logits_out,
+                flags_out, stream=None) -> None:
+    """The paper's main gate: x [B, L, d]; w_qkv [d, 3*h'*d'] (Q'|K'|V', head-major inside); w_o [h'*d', H_f];
+    bias f32 [H_f]; logits_out f32 [B, L, H_f] or None; flags_out u8 [B, H_f, L]."""
+    B, L, d = x.shape
+    H_f = w_o.shape[1]
+    ctx._check(ctx._lib.ag_gate_mha(ctx._h, _stream_ptr(stream), _ptr(x), _dtype_code(x), B, L, d, _ptr(w_qkv),
+                                    h_prime, d_prime, _ptr(w_o), _ptr(bias), H_f, tau, n_sink, _ptr(logits_out),
+                                    _ptr(flags_out)))

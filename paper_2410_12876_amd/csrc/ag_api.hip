@@ -115,7 +115,8 @@ void ag_destroy(ag_ctx *ctx) {
 }
 
 static const char *const kKernelNames[AG_K_COUNT] = {"gate", "gate_finalize", "flag_scan", "compact",
-                                                     "prefill", "decode_partial", "decode_merge"};
+                                                     "prefill", "decode_partial", "decode_merge",
+                                                     "mha_proj", "mha_attn"};
 
 int ag_timing_kernels(void) { return AG_K_COUNT; }
 
@@ -230,6 +231,39 @@ ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtyp
   hipError_t e = ag_launch_gate(ctx, (hipStream_t)hip_stream, feat, dtype, B, L, d_in, w_gate, bias, H_f, thr,
                                 n_sink, logits_out, flags_out, ws);
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_gate: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes, ws.off);
+  AG_HIP(e);
+  return AG_OK;
+}
+
+size_t ag_gate_mha_workspace_bytes(int B, int L, int d_model, int h_prime, int d_prime, int H_f) {
+  if (B <= 0 || L <= 0 || d_model <= 0 || h_prime <= 0 || d_prime != 128 || H_f <= 0) return 0;
+  return ag_ws_gate_mha_bytes(B, L, d_model, h_prime, H_f);
+}
+
+ag_status ag_gate_mha(ag_ctx *ctx, void *hip_stream, const void *x, ag_dtype dtype, int B, int L, int d_model,
+                      const void *w_qkv, int h_prime, int d_prime, const void *w_o, const float *bias, int H_f,
+                      float tau, int n_sink, float *logits_out, uint8_t *flags_out) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(x && w_qkv && w_o && bias && flags_out, AG_EINVAL, "ag_gate_mha: null pointer");
+  AG_REQUIRE(B > 0 && L > 0 && d_model > 0 && h_prime > 0 && d_prime > 0 && H_f > 0, AG_EINVAL,
+             "ag_gate_mha: sizes must be positive");
+  AG_REQUIRE(tau > 0.f && tau < 1.f, AG_EINVAL, "ag_gate_mha: tau must lie in (0, 1)");
+  AG_REQUIRE(n_sink >= 0, AG_EINVAL, "ag_gate_mha: n_sink is negative");
+  AG_REQUIRE(dtype_ok(dtype), AG_EINVAL, "ag_gate_mha: unknown dtype %d", (int)dtype);
+  AG_REQUIRE(dtype == AG_BF16 && d_prime == 128, AG_EUNSUPPORTED, "ag_gate_mha: only bf16 with d_prime = 128 is built");
+  AG_REQUIRE(d_model % 64 == 0, AG_EUNSUPPORTED, "ag_gate_mha: d_model %% 64 != 0 (got %d)", d_model);
+  AG_REQUIRE(H_f <= 32, AG_EUNSUPPORTED, "ag_gate_mha: H_f = %d exceeds 32", H_f);
+  AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_gate_mha: L = %d exceeds %d", L, kMaxL);
+  AG_REQUIRE((int64_t)B * h_prime <= 65535 && (int64_t)d_model * 3 * h_prime * 128 < (1ll << 30) &&
+                 (int64_t)B * L < (1ll << 31) - 128,
+             AG_EUNSUPPORTED, "ag_gate_mha: problem too large");
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  const float thr = (float)log((double)tau / (1.0 - (double)tau));
+  ws_cursor ws = cursor(ctx);
+  hipError_t e = ag_launch_gate_mha(ctx, (hipStream_t)hip_stream, x, B, L, d_model, w_qkv, h_prime, w_o, bias, H_f, thr,
+                                    n_sink, 1.0f / sqrtf((float)d_prime), logits_out, flags_out, ws);
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_gate_mha: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes, ws.off);
   AG_HIP(e);
   return AG_OK;
 }

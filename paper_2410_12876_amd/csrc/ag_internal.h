@@ -8,7 +8,7 @@
 
 // Kernels that ag_timing_* can time (ids are part of the ABI, see ag.h).
 enum { AG_K_GATE = 0, AG_K_GATE_FINALIZE, AG_K_FLAG_SCAN, AG_K_COMPACT, AG_K_PREFILL, AG_K_DECODE_PARTIAL,
-       AG_K_DECODE_MERGE, AG_K_COUNT };
+       AG_K_DECODE_MERGE, AG_K_MHA_PROJ, AG_K_MHA_ATTN, AG_K_COUNT };
 constexpr int kTimerSlots = 1024;  // launches remembered per kernel id
 
 struct ag_timer {
@@ -102,7 +102,13 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
                                   const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
                                   const void *kc, const void *vc, const int64_t *row_off, void *out,
-                                  const ag_pf_plan &plan, float *part);
+                                  const ag_pf_plan &plan, float *part, bool out_token_major = false);
+
+// The paper's main gate: MHA' (projection GEMM, causal attention with hp heads of 128) in front of ag_launch_gate.
+size_t ag_ws_gate_mha_bytes(int B, int L, int d_model, int hp, int H_f);
+hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, int L, int d_model, const void *w_qkv,
+                              int hp, const void *w_o, const float *bias, int H_f, float thr, int n_sink, float scale,
+                              float *logits, uint8_t *flags, ws_cursor &ws);
 
 // Device view of an ag_recent_ring (k == nullptr: no ring).  Slot w of unit u is element u * n + w.
 struct ag_ring_dev {

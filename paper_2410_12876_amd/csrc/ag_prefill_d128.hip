@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw, int n_hy,
     int n_split, const int32_t *__restrict__ chunk_tiles_dev, float qscale, int n_recent,
-    const int32_t *__restrict__ order, uint16_t *__restrict__ out, float *__restrict__ part,
+    const int32_t *__restrict__ order, uint16_t *__restrict__ out, int out_token_major, float *__restrict__ part,
     int32_t *__restrict__ tickets) {
   constexpr int QW = 4 / GB;   // query sub-tiles per workgroup
   constexpr int BM = 32 * QW;  // queries per workgroup
@@ -499,7 +499,8 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (j0 + col < L) {
     const float inv = 1.f / l_tot;
-    uint16_t *orow = out + qrow;
+    // head-major [B, Hq, L, D] like q, or token-major [B, L, Hq, D] (heads of a token side by side)
+    uint16_t *orow = out + (out_token_major ? (((size_t)b * L + jq) * Hq + head) * D : qrow);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -550,7 +551,7 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
                                   const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
                                   const void *kc, const void *vc, const int64_t *row_off, void *out,
-                                  const ag_pf_plan &plan, float *part) {
+                                  const ag_pf_plan &plan, float *part, bool out_token_major) {
   (void)B;
   const int nw = ag_nwords(L);
   const int G = Hq / Hkv;
@@ -561,7 +562,7 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
   hipLaunchKernelGGL((ag_prefill_d128_kernel<GG, BB>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k,    \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
                      Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, n_recent, plan.order,               \
-                     (uint16_t *)out, part, plan.tickets)
+                     (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)
   if (n_recent > 1) {
     if (GB == 1) AG_PF(1, true); else if (GB == 2) AG_PF(2, true); else AG_PF(4, true);
   } else {

@@ -390,3 +390,49 @@ def test_decode_recent_window_against_the_prefill_definition(dtype, B, Hq, Hkv, 
         assert np.array_equal(rk[:, p % n_recent], k_all.f32[:, :, p].reshape(U, D))
     ctx.poll_error()
     ctx.close()
+
+
+# --------------------------------------------------------------------------------- main gate module (MHA')
+def _gate_mha_case(B, L, d, hp, H, seed, tau=0.5, n_sink=0):
+    g = np.random.default_rng(seed)
+    x = W.store(g.standard_normal((B, L, d)).astype(np.float32) * 0.5, "bf16")
+    wqkv = W.store(g.standard_normal((d, 3 * hp * 128)).astype(np.float32) / math.sqrt(d) * 2.0, "bf16")
+    wo = W.store(g.standard_normal((hp * 128, H)).astype(np.float32) / math.sqrt(hp * 128), "bf16")
+    bias = (g.standard_normal(H) * 0.1).astype(np.float32)
+    ctx = ag.Context(0, ag.gate_mha_workspace_bytes(B, L, d, hp, 128, H))
+    logits = torch.empty(B, L, H, dtype=torch.float32, device=DEV)
+    flags = torch.empty(B, H, L, dtype=torch.uint8, device=DEV)
+    ag.ag_gate_mha(ctx, dev(x), dev(wqkv), hp, 128, dev(wo), dev(bias), tau, n_sink, logits, flags)
+    torch.cuda.synchronize()
+    ctx.close()
+    ref_logits, ref_flags = oracle.gate_mha(x.f32, wqkv.f32, hp, 128, wo.f32, bias, tau, n_sink, store="bf16")
+    return logits.cpu().numpy(), flags.cpu().numpy(), ref_logits, ref_flags
+
+
+@pytest.mark.parametrize("B,L,d,hp,H,n_sink", [(1, 300, 256, 4, 8, 0), (2, 129, 512, 2, 32, 2), (1, 1000, 1024, 4, 32, 0),
+                                               (3, 64, 128, 1, 4, 1)])
+def test_gate_mha_against_oracle(B, L, d, hp, H, n_sink):
+    """The paper's main gate (MHA' front end + projection).  Q', K', V' and the attention output are bf16 tensors
+    on both sides; flags are compared where the oracle's logit is further than 2e-2 from the threshold (the
+    band that the bf16 storage of those tensors can move a logit by), the rest is counted."""
+    tau = 0.45
+    logits, flags, ref_logits, ref_flags = _gate_mha_case(B, L, d, hp, H, 130 + L, tau, n_sink)
+    err = np.abs(logits - ref_logits).max()
+    scale = np.sqrt(np.mean(ref_logits ** 2))
+    near = (np.abs(ref_logits - oracle.logit_threshold(tau)) < 2e-2).transpose(0, 2, 1)
+    print("gate_mha B%d L%d d%d h'%d: logit max-abs err %.3g (logit RMS %.3g); %d of %d within the band, %d flags differ"
+          % (B, L, d, hp, err, scale, int(near.sum()), near.size, int((flags != ref_flags).sum())))
+    assert err <= 1e-2
+    assert np.array_equal(flags[~near], ref_flags[~near])
+    assert (flags[:, :, :n_sink] == 1).all()
+
+
+def test_gate_mha_full_size_llama2_7b_shape():
+    """The gate module at the paper's size (d = 4096, h' = 4, d'_k = 128, 32 flag columns) on a 4096-token prompt."""
+    tau = 0.5
+    logits, flags, ref_logits, ref_flags = _gate_mha_case(1, 4096, 4096, 4, 32, 140, tau, 0)
+    err = np.abs(logits - ref_logits).max()
+    near = (np.abs(ref_logits - oracle.logit_threshold(tau)) < 2e-2).transpose(0, 2, 1)
+    print("gate_mha full size: logit max-abs err %.3g (logit RMS %.3g); %d of %d within the band, %d flags differ"
+          % (err, np.sqrt(np.mean(ref_logits ** 2)), int(near.sum()), near.size, int((flags != ref_flags).sum())))
+    assert err <= 1e-2 and np.array_equal(flags[~near], ref_flags[~near])
