@@ -54,6 +54,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 #define AG_LDS __attribute__((address_space(3)))
 
 constexpr int D = 128;
@@ -212,20 +214,71 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   if (n_steps > 0) { issue_k(0); issue_v(0); }
   if (n_steps > 1) issue_k(1);
 
-  // ---- Q fragments (B operand of S^T): lane (query col, half hb), k-step ks: Q[j][16 ks + 8 hb .. +8) ----
-  // Q and, for chunk 0, the query's own key and value rows are all requested before anything waits on them.
+  // ---- Q fragments (B operand of S^T): lane (query col, half hb), k-step ks: Q[j][16 ks + 8 hb .. +8); for chunk 0
+  // also the query's own key row (same layout) and value row (lane: d = 32 dt + 8 r4 + 4 hb .. +4) ----
+  // A lane needs 16-byte pieces of ITS query's row, so direct loads would touch 64 different cache lines per
+  // instruction (measured: 4.5 us of a workgroup's 7 us start-up).  Instead the wave reads its 32 rows with
+  // whole-line loads (lane -> row 4 j + lane/16, 16-byte chunk lane%16: 1 KiB contiguous per instruction) and turns
+  // them into fragments through a private 4 KiB corner of the V1 tile buffer, 16 rows at a time; V1 is not a
+  // load target before the first step.  Chunks are XOR-swizzled with the row so that both sides are conflict-free.
   uint4 qf[KS], kself[KS];
   uint2 vself[DT][4];
+  {
+    const int srow = lane >> 4, schunk = lane & 15;
+    u32x4 sq[2][4], sk[2][4], sv[2][4];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const uint4 *>(q + qrow + 16 * ks + 8 * hb);
-  if (chunk == 0) {
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kself[ks] = *reinterpret_cast<const uint4 *>(k + kvrow + 16 * ks + 8 * hb);
+      for (int j = 0; j < 4; ++j) {
+        const int row = min(j0 + 16 * h + 4 * j + srow, L - 1);
+        // (all three unconditionally: the few workgroups that hold a later chunk of a split item do not use k, v)
+        sq[h][j] = *reinterpret_cast<const u32x4 *>(q + ((size_t)(b * Hq + head) * L + row) * D + 8 * schunk);
+        sk[h][j] = *reinterpret_cast<const u32x4 *>(k + ((size_t)u * L + row) * D + 8 * schunk);
+        sv[h][j] = *reinterpret_cast<const u32x4 *>(v + ((size_t)u * L + row) * D + 8 * schunk);
+      }
+    AG_LDS uint8_t *stage = (AG_LDS uint8_t *)smem + 3 * kTileB + w4 * 4096;
+    const int rr = col & 15;  // this lane's row inside a 16-row pass
+    auto put = [&](const u32x4 (&x)[4]) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+      for (int j = 0; j < 4; ++j) {
+        const int r = 4 * j + srow;
+        *reinterpret_cast<AG_LDS u32x4 *>(stage + r * 256 + ((schunk ^ r) << 4)) = x[j];
+      }
+    };
+    auto get4 = [&](int off) {
+      const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(stage + off);
+      return make_uint4(x[0], x[1], x[2], x[3]);
+    };
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-        vself[dt][r4] = *reinterpret_cast<const uint2 *>(v + kvrow + 32 * dt + 8 * r4 + 4 * hb);
+    for (int h = 0; h < 2; ++h) {
+      const bool mine = (col >> 4) == h;
+      put(sq[h]);
+      if (mine) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          qf[ks] = get4(rr * 256 + (((2 * ks + hb) ^ rr) << 4));
+      }
+      if (chunk == 0) {
+        put(sk[h]);
+        if (mine) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            kself[ks] = get4(rr * 256 + (((2 * ks + hb) ^ rr) << 4));
+        }
+        put(sv[h]);
+        if (mine) {
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+            {
+              const u32x2 x = *reinterpret_cast<const AG_LDS u32x2 *>(stage + rr * 256 + (((4 * dt + r4) ^ rr) << 4) + 8 * hb);
+              vself[dt][r4] = make_uint2(x[0], x[1]);
+            }
+        }
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the corner is read out before anyone may load V(1) over it
   }
   __builtin_amdgcn_sched_barrier(0);  // keep the loads above ahead of the arithmetic below
 
