@@ -3,7 +3,8 @@
 
 One "step" is one pass of the whole path over one Llama2-7B-shaped layer (config 2: bf16, B=1, L=4096,
 d=4096, 32 heads x 128, per-head keep ratios U[0.2, 0.9]):
-    ag_gate -> ag_compact_kv -> ag_prefill_attn (over the compacted cache) -> one ag_decode_attn step.
+    ag_gate -> ag_compact_prefill_attn (= ag_compact_kv + ag_prefill_attn over the compacted cache, sharing one
+    flag scan) -> one ag_decode_attn step.
 `value` is prompt tokens per second through that step, inputs resident in HBM.  The same JSON line carries
   roofline      : the dominant kernel (masked prefill attention) against the bf16 MFMA peak,
   decode        : config 3 (B=32, ragged caches ~ round(4096 U[0.1,1]), Bernoulli(0.5) appends), 256 decode
@@ -72,8 +73,7 @@ def prefill_leg(args, torch, ag, W):
 
     def step():
         ag.ag_gate(ctx, x, wg, bias, wl.tau, wl.n_sink, None, flags)
-        ag.ag_compact_kv(ctx, k, v, flags, 0, cache)
-        ag.ag_prefill_attn(ctx, q, k, v, flags, wl.scale, cache, out)
+        ag.ag_compact_prefill_attn(ctx, q, k, v, flags, wl.scale, 0, cache, out)   # compaction + attention, one flag scan
         ag.ag_decode_attn(ctx, dq, dk, dv, None, L, wl.scale, cache, dout)
 
     for _ in range(args.warmup):

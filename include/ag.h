@@ -167,6 +167,15 @@ ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, c
                                  float scale, const ag_kv_cache *cache, int n_recent, void *out);
 
 /*
+ * ag_compact_kv followed by ag_prefill_attn_recent on the same k, v, flags, as one call that scans the flags once:
+ * `cache` (row_off filled by the caller) receives the compacted rows, idx (pos0 + t) and len exactly as from
+ * ag_compact_kv, and out the attention over them.  The prefilling stage of one layer (Sec. 3.1, Sec. 3.3).
+ */
+ag_status ag_compact_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                                  const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype,
+                                  float scale, int pos0, ag_kv_cache *cache, int n_recent, void *out);
+
+/*
  * One decoding step (Sec. 3.1 decoding stage; the gate is not run during decoding, Sec. 3.4).
  * For every (b, query head i): keys = cache rows of unit (b, g) followed by k_new[b,g]; same for values;
  * out[b,i,:] = softmax-weighted sum (the new token always attends to itself, Eq. 5 diagonal; an empty cache

@@ -21,7 +21,7 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
            "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
-           "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
+           "ag_compact_prefill_attn", "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
 
 
 class ag_recent_ring(C.Structure):
@@ -85,6 +85,9 @@ def load() -> C.CDLL:
     lib.ag_prefill_attn_recent.restype = C.c_int
     lib.ag_prefill_attn_recent.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32,
                                            C.POINTER(ag_kv_cache), i32, vp]
+    lib.ag_compact_prefill_attn.restype = C.c_int
+    lib.ag_compact_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32,
+                                            C.POINTER(ag_kv_cache), i32, vp]
     lib.ag_decode_attn.restype = C.c_int
     lib.ag_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache), vp]
     lib.ag_gate_mha_workspace_bytes.restype = C.c_size_t
@@ -231,6 +234,16 @@ def ag_prefill_attn_recent(ctx: Context, q, k, v, flags, scale: float, cache: Op
     ctx._check(ctx._lib.ag_prefill_attn_recent(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k), _ptr(v), _ptr(flags),
                                                B, L, Hq, Hkv, D, _dtype_code(q), scale,
                                                C.byref(cache.c) if cache is not None else None, n_recent, _ptr(out)))
+
+
+def ag_compact_prefill_attn(ctx: Context, q, k, v, flags, scale: float, pos0: int, cache: KVCache, out,
+                            n_recent: int = 1, stream=None) -> None:
+    """ag_compact_kv + ag_prefill_attn in one call (one flag scan): fills `cache` and `out`."""
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    ctx._check(ctx._lib.ag_compact_prefill_attn(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k), _ptr(v), _ptr(flags),
+                                                B, L, Hq, Hkv, D, _dtype_code(q), scale, pos0, C.byref(cache.c),
+                                                n_recent, _ptr(out)))
 
 
 def ag_decode_attn(ctx: Context, q, k_new, v_new, new_flags, pos: int, scale: float, cache: KVCache, out,

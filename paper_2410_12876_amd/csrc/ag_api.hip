@@ -299,10 +299,16 @@ ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const vo
   return ag_prefill_attn_recent(ctx, hip_stream, q, k, v, flags, B, L, Hq, Hkv, D, dtype, scale, cache, 1, out);
 }
 
-ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
-                                 const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype,
-                                 float scale, const ag_kv_cache *cache, int n_recent, void *out) {
+}  // extern "C"
+
+namespace {
+// ag_prefill_attn[_recent] (fill_cache == false: `cache`, if given, already holds the compacted rows) and
+// ag_compact_prefill_attn (fill_cache == true: the call's own scan also drives the compaction into `cache`).
+ag_status prefill_common(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                         const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, float scale,
+                         const ag_kv_cache *cache, int n_recent, void *out, bool fill_cache, int pos0) {
   if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(!fill_cache || cache, AG_EINVAL, "ag_compact_prefill_attn: cache is NULL");
   AG_REQUIRE(n_recent >= 1 && n_recent <= 64, AG_EINVAL, "ag_prefill_attn: n_recent = %d outside [1, 64]", n_recent);
   AG_REQUIRE(q && k && v && flags && out, AG_EINVAL, "ag_prefill_attn: null pointer");
   AG_REQUIRE(B > 0 && L > 0 && Hq > 0 && Hkv > 0 && D > 0, AG_EINVAL, "ag_prefill_attn: sizes must be positive");
@@ -354,10 +360,29 @@ ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, c
   if (!cache) {
     AG_HIP(ag_launch_slab_offsets(s, wro, units, L));
     AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(D * esz), 0, wk, wv, widx, wro, wlen));
+  } else if (fill_cache) {
+    AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(D * esz), pos0, cache->k, cache->v,
+                             cache->idx, cache->row_off, cache->len));
   }
   AG_HIP(ag_launch_prefill(ctx, s, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, n_recent, kc, vc, row_off,
                            out, plan, part));
   return AG_OK;
+}
+}  // namespace
+
+extern "C" {
+
+ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                                 const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype,
+                                 float scale, const ag_kv_cache *cache, int n_recent, void *out) {
+  return prefill_common(ctx, hip_stream, q, k, v, flags, B, L, Hq, Hkv, D, dtype, scale, cache, n_recent, out, false, 0);
+}
+
+ag_status ag_compact_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
+                                  const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype,
+                                  float scale, int pos0, ag_kv_cache *cache, int n_recent, void *out) {
+  return prefill_common(ctx, hip_stream, q, k, v, flags, B, L, Hq, Hkv, D, dtype, scale, cache, n_recent, out, true,
+                        pos0);
 }
 
 namespace {

@@ -436,3 +436,27 @@ def test_gate_mha_full_size_llama2_7b_shape():
     print("gate_mha full size: logit max-abs err %.3g (logit RMS %.3g); %d of %d within the band, %d flags differ"
           % (err, np.sqrt(np.mean(ref_logits ** 2)), int(near.sum()), near.size, int((flags != ref_flags).sum())))
     assert err <= 1e-2 and np.array_equal(flags[~near], ref_flags[~near])
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,L,D", [("bf16", 1, 16, 16, 2048, 128), ("bf16", 2, 8, 2, 300, 64), ("f32", 1, 4, 4, 128, 64)])
+def test_compact_prefill_in_one_call_equals_the_two_calls(dtype, B, Hq, Hkv, L, D):
+    """ag_compact_prefill_attn (one flag scan) leaves the same cache and the same output, bit for bit, as
+    ag_compact_kv followed by ag_prefill_attn."""
+    g = np.random.default_rng(150 + L)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    q, k, v = (dev(W.store(g.standard_normal(s).astype(np.float32), dtype))
+               for s in ((B, Hq, L, D), (B, Hkv, L, D), (B, Hkv, L, D)))
+    flags = dev((g.random((B, Hkv, L)) < np.linspace(0.1, 0.9, Hkv)[None, :, None]).astype(np.uint8))
+    scale = 1.0 / math.sqrt(D)
+    ro = oracle.slab_row_off(B * Hkv, L)
+    ctx = make_ctx(B, L, Hq, Hkv, D, ag.AG_BF16 if dtype == "bf16" else ag.AG_F32)
+    c1, c2 = new_cache(B, Hkv, D, tdt, ro), new_cache(B, Hkv, D, tdt, ro)
+    o1, o2 = torch.empty_like(q), torch.empty_like(q)
+    ag.ag_compact_kv(ctx, k, v, flags, 7, c1)
+    ag.ag_prefill_attn(ctx, q, k, v, flags, scale, c1, o1)
+    ag.ag_compact_prefill_attn(ctx, q, k, v, flags, scale, 7, c2, o2)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    ctx.close()
+    assert torch.equal(o1, o2) and torch.equal(c1.len, c2.len) and torch.equal(c1.idx, c2.idx)
+    assert torch.equal(c1.k, c2.k) and torch.equal(c1.v, c2.v)
