@@ -200,6 +200,60 @@ def decode_leg(args, torch, ag, W):
     return res, wl
 
 
+def overlap_leg(args, torch, ag, W, wl):
+    """Several layers back to back: the gate of layer l+1 takes its input from before layer l's attention
+    (previous-layer gating, Table 3), so it can run on a second stream (own context and workspace) beside layer
+    l's compaction + attention.  Reports ms per layer with the gates in line and with the gates on the side."""
+    B, L, Hq, Hkv, D, d = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D, wl.d_model
+    layers, U, cap = 8, wl.B * wl.Hkv, wl.L + 8
+    x, wg, bias = to_dev(wl.x, torch), to_dev(wl.w_gate, torch), torch.from_numpy(wl.bias).cuda()
+    q, k, v = to_dev(wl.q, torch), to_dev(wl.k, torch), to_dev(wl.v, torch)
+    out = torch.empty_like(q)
+    ro = torch.from_numpy(np.arange(U + 1, dtype=np.int64) * cap).cuda()
+    cache = ag.KVCache(torch.zeros(U * cap, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(U * cap, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(U * cap, dtype=torch.int32, device="cuda"), ro,
+                       torch.zeros(U, dtype=torch.int32, device="cuda"), B, Hkv, D)
+    flags = [torch.empty(B, Hkv, L, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    ws = ag.workspace_bytes(B, L, Hq, Hkv, D, ag.AG_BF16, d, U * cap)
+    ctx_a, ctx_g = ag.Context(0, ws), ag.Context(0, ws)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    ready = [torch.cuda.Event() for _ in range(2)]
+    used = [torch.cuda.Event() for _ in range(2)]
+
+    def run(overlap):
+        gs, gctx = (side, ctx_g) if overlap else (main, ctx_a)
+        gs.wait_stream(main)
+        with torch.cuda.stream(gs):
+            ag.ag_gate(gctx, x, wg, bias, wl.tau, wl.n_sink, None, flags[0])
+            ready[0].record(gs)
+        for l in range(layers):
+            if l + 1 < layers:
+                with torch.cuda.stream(gs):
+                    gs.wait_event(used[(l + 1) & 1]) if l >= 1 else None   # the flag buffer's previous reader is done
+                    ag.ag_gate(gctx, x, wg, bias, wl.tau, wl.n_sink, None, flags[(l + 1) & 1])
+                    ready[(l + 1) & 1].record(gs)
+            main.wait_event(ready[l & 1])
+            ag.ag_compact_prefill_attn(ctx_a, q, k, v, flags[l & 1], wl.scale, 0, cache, out)
+            used[l & 1].record(main)
+        main.wait_stream(gs)
+
+    res = {}
+    for name, ov in (("gates_in_line", False), ("gates_on_second_stream", True)):
+        for _ in range(2):
+            run(ov)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run(ov)
+        torch.cuda.synchronize()
+        res[name + "_ms_per_layer"] = (time.perf_counter() - t0) / args.steps / layers * 1e3
+    ctx_a.close()
+    ctx_g.close()
+    res["layers"] = layers
+    return res
+
+
 def cpu_baseline(wl, W):
     """The oracle, as it stands, on the whole config-2 step (gate over all tokens and heads, compaction, masked
     prefill, one decode step) on the host cores; its one OpenMP loop runs over the 32 (batch, head) units."""
@@ -265,6 +319,7 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching it eagerly")
     ap.add_argument("--skip-decode", action="store_true")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-overlap", action="store_true", help="skip the multi-layer gate-overlap measurement")
     ap.add_argument("--skip-machine", action="store_true", help="skip the MFMA / copy / vendor-GEMM probes")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -294,6 +349,7 @@ def main():
     if not args.skip_cpu_baseline:
         log("[bench] timing the CPU oracle on one step ...")
         cpu = cpu_baseline(wl, W)
+    overlap = None if args.skip_overlap else overlap_leg(args, torch, ag, W, wl)
     machine = None if args.skip_machine else machine_context(torch, ag)
     if machine:
         pre["roofline"]["frac_of_vendor_gemm"] = pre["roofline"]["achieved"] / machine["vendor_gemm_bf16_8192_tflops"]
@@ -307,7 +363,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": pre["config"], "kernel_ms": pre["kernel_ms"], "roofline": pre["roofline"],
         "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
-        "machine": machine,
+        "next_layer_gate_overlap": overlap, "machine": machine,
     }
     print(json.dumps(line))
 

@@ -460,3 +460,52 @@ def test_compact_prefill_in_one_call_equals_the_two_calls(dtype, B, Hq, Hkv, L, 
     ctx.close()
     assert torch.equal(o1, o2) and torch.equal(c1.len, c2.len) and torch.equal(c1.idx, c2.idx)
     assert torch.equal(c1.k, c2.k) and torch.equal(c1.v, c2.v)
+
+
+def test_gate_of_the_next_layer_overlaps_on_a_second_stream():
+    """Previous-layer gating (Table 3, the settings that take the gate's input from the layer before): the flags
+    of layer l+1 do not depend on layer l's attention, so its gate can run on a second stream (own context, own
+    workspace, default priority) while layer l compacts and attends.  Results must equal the sequential run."""
+    B, H, L, D, d, layers = 1, 16, 2048, 128, 1024, 3
+    g = np.random.default_rng(160)
+    xs = [dev(W.store(g.standard_normal((B, L, d)).astype(np.float32) * 0.5, "bf16")) for _ in range(layers)]
+    wg = [dev(W.store(g.standard_normal((d, H)).astype(np.float32) / 32.0, "bf16")) for _ in range(layers)]
+    bias = dev(np.zeros(H, np.float32))
+    qkv = [[dev(W.store(g.standard_normal((B, H, L, D)).astype(np.float32), "bf16")) for _ in range(3)] for _ in range(layers)]
+    scale = 1.0 / math.sqrt(D)
+    ro = oracle.slab_row_off(B * H, L)
+
+    def run(overlap):
+        main = torch.cuda.current_stream()
+        side = torch.cuda.Stream() if overlap else main
+        ctx_a = make_ctx(B, L, H, H, D, ag.AG_BF16, d_in=d)
+        ctx_g = make_ctx(B, L, H, H, D, ag.AG_BF16, d_in=d) if overlap else ctx_a
+        flags = [torch.empty(B, H, L, dtype=torch.uint8, device=DEV) for _ in range(layers)]
+        outs = [torch.empty_like(qkv[0][0]) for _ in range(layers)]
+        caches = [new_cache(B, H, D, torch.bfloat16, ro) for _ in range(layers)]
+        ready = [torch.cuda.Event() for _ in range(layers)]
+        side.wait_stream(main)
+        with torch.cuda.stream(side):
+            ag.ag_gate(ctx_g, xs[0], wg[0], bias, 0.5, 0, None, flags[0])
+            ready[0].record(side)
+        for l in range(layers):
+            if l + 1 < layers:      # the gate of the next layer: enqueued before, runs beside, this layer's attention
+                with torch.cuda.stream(side):
+                    ag.ag_gate(ctx_g, xs[l + 1], wg[l + 1], bias, 0.5, 0, None, flags[l + 1])
+                    ready[l + 1].record(side)
+            main.wait_event(ready[l])
+            q, k, v = qkv[l]
+            ag.ag_compact_prefill_attn(ctx_a, q, k, v, flags[l], scale, 0, caches[l], outs[l])
+        main.wait_stream(side)
+        torch.cuda.synchronize()
+        ctx_a.poll_error()
+        ctx_a.close()
+        if overlap:
+            ctx_g.close()
+        return flags, outs, caches
+
+    f0, o0, c0 = run(False)
+    f1, o1, c1 = run(True)
+    for l in range(layers):
+        assert torch.equal(f0[l], f1[l]) and torch.equal(o0[l], o1[l])
+        assert torch.equal(c0[l].len, c1[l].len) and torch.equal(c0[l].k, c1[l].k)
