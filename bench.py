@@ -49,8 +49,18 @@ def visible_pairs(flags: np.ndarray, G: int) -> int:
     return int((cnt + 1).sum()) * G
 
 
+def make_workload(args, W):
+    """--config 2 (default, the headline workload), 4 (Llama-3-8B GQA shape, L = 32768, flags given as runs) or
+    5 (one layer of the 32-layer stack, B = 16, L = 2048; --layer picks it)."""
+    if args.config == 4:
+        return W.config4(with_x=True)
+    if args.config == 5:
+        return W.config5_layer(args.layer)
+    return W.config2(L=args.seq_len, keep=None if args.keep is None else np.full(32, args.keep))
+
+
 def prefill_leg(args, torch, ag, W):
-    wl = W.config2(L=args.seq_len, keep=None if args.keep is None else np.full(32, args.keep))
+    wl = make_workload(args, W)
     B, L, Hq, Hkv, D, d = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D, wl.d_model
     G = Hq // Hkv
     U = B * Hkv
@@ -60,6 +70,9 @@ def prefill_leg(args, torch, ag, W):
     x, wg, bias = to_dev(wl.x, torch), to_dev(wl.w_gate, torch), torch.from_numpy(wl.bias).cuda()
     q, k, v = to_dev(wl.q, torch), to_dev(wl.k, torch), to_dev(wl.v, torch)
     flags = torch.empty(B, Hkv, L, dtype=torch.uint8, device="cuda")
+    # config 4 gives its flags (run-structured); the gate still runs in the step, into a buffer of its own
+    given = None if wl.flags is None else torch.from_numpy(wl.flags).cuda()
+    pf_flags = flags if given is None else given
     out = torch.empty_like(q)
     ro = np.arange(U + 1, dtype=np.int64) * cap
     cache = ag.KVCache(torch.zeros(rows, D, dtype=torch.bfloat16, device="cuda"),
@@ -73,7 +86,7 @@ def prefill_leg(args, torch, ag, W):
 
     def step():
         ag.ag_gate(ctx, x, wg, bias, wl.tau, wl.n_sink, None, flags)
-        ag.ag_compact_prefill_attn(ctx, q, k, v, flags, wl.scale, 0, cache, out)   # compaction + attention, one flag scan
+        ag.ag_compact_prefill_attn(ctx, q, k, v, pf_flags, wl.scale, 0, cache, out)   # compaction + attention, one flag scan
         ag.ag_decode_attn(ctx, dq, dk, dv, None, L, wl.scale, cache, dout)
 
     for _ in range(args.warmup):
@@ -118,7 +131,7 @@ def prefill_leg(args, torch, ag, W):
     ctx.timing_enable(False)
     ctx.poll_error()
 
-    fl = flags.cpu().numpy()
+    fl = pf_flags.cpu().numpy()
     pairs = visible_pairs(fl, G)
     flops = 4.0 * D * pairs
     kept_rows = int(fl.sum())
@@ -132,12 +145,14 @@ def prefill_leg(args, torch, ag, W):
         "keep_ratio": float(fl.mean()),
         "roofline": {"kernel": "ag_prefill_d128_kernel<1>", "bound": "mfma", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": TRAFFIC_BYTES.get(("prefill", L)) if args.keep is None else None, "flops_per_launch": flops, "visible_pairs": pairs,
+                     "traffic": TRAFFIC_BYTES.get(("prefill", L)) if args.keep is None and args.config == 2 else None, "flops_per_launch": flops, "visible_pairs": pairs,
                      "avg_launch_ms": pf_ms},
         "compact_gbs": (2 * 2 * kept_rows * D * 2 + fl.size + 4 * kept_rows) / (per_kernel["compact"] * 1e-3) / 1e9,
         "gate_gbs": (B * L * d * 2) / (per_kernel["gate"] * 1e-3) / 1e9,
         "config": {"workload": wl.name, "B": B, "L": L, "d_model": d, "Hq": Hq, "Hkv": Hkv, "D": D,
-                   "keep": ("per-head U[0.2,0.9]" if args.keep is None else "every head %.2f" % args.keep) + ", mean %.3f" % fl.mean(),
+                   "keep": ("given as runs" if args.config == 4 else "per layer and head" if args.config == 5 else
+                            "per-head U[0.2,0.9]" if args.keep is None else "every head %.2f" % args.keep) +
+                           ", mean %.3f" % fl.mean(),
                    "launch": "hip graph replay" if graph is not None else "eager"},
     }
     ctx.close()
@@ -272,8 +287,17 @@ def cpu_baseline(wl, W):
     oracle.decode_step(dq, dk, dv, None, L, c32, wl.scale)
     t1 = time.perf_counter()
     t = (t_mid - t0) + (t1 - t_mid2)
-    return {"value": wl.B * L / t, "unit": "tokens/s", "cores": min(oracle.threads(), wl.B * H), "kind": "oracle",
-            "sample": "one whole config-2 step (all %d heads, L=%d): %.2f s" % (H, L, t), "seconds_sample": t}
+    # one thread, on the masked prefill of 2 of the heads (the step's dominant part), scaled to all heads
+    n_thr = oracle.threads()
+    oracle.set_threads(1)
+    s0 = time.perf_counter()
+    oracle.prefill_attn(wl.q.f32[:, :2], wl.k.f32[:, :2], wl.v.f32[:, :2], f[:, :2], wl.scale)
+    t_one = (time.perf_counter() - s0) * H / 2
+    oracle.set_threads(n_thr)
+    return {"value": wl.B * L / t, "unit": "tokens/s", "cores": min(n_thr, wl.B * H), "kind": "oracle",
+            "sample": "one whole config-2 step (all %d heads, L=%d): %.2f s" % (H, L, t), "seconds_sample": t,
+            "one_thread_prefill_tokens_per_s": wl.B * L / t_one,
+            "one_thread_sample": "masked prefill of 2 heads on 1 thread, scaled to %d heads: %.1f s" % (H, t_one)}
 
 
 # HBM bytes per launch from the rocprofv3 counter passes summarised in
@@ -311,6 +335,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[2, 4, 5],
+                    help="prefill workload: 2 = headline (default); 4, 5 = the other layer-shaped configurations")
+    ap.add_argument("--layer", type=int, default=16, help="layer of config 5")
     ap.add_argument("--seq-len", type=int, default=4096)
     ap.add_argument("--keep", type=float, default=None,
                     help="one keep ratio for every head instead of config 2's per-head U[0.2, 0.9]")
@@ -337,9 +364,11 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
 
-    log("[bench] generating config 2 ...")
+    log("[bench] generating config %d ..." % args.config)
     pre, wl, flags = prefill_leg(args, torch, ag, W)
     log("[bench] prefill leg done: %.3f ms/step" % (pre["seconds"] / args.steps * 1e3))
+    if args.config != 2:  # the other legs are defined on the headline workload
+        args.skip_decode = args.skip_cpu_baseline = args.skip_overlap = True
     dec = None
     if not args.skip_decode:
         log("[bench] generating config 3 ...")

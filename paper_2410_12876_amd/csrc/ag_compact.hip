@@ -100,11 +100,14 @@ __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_
   if (plan.order) {
     // Head blocks are ranked by the kept rows of their unit and dealt to the 8 XCDs in snake order
     // (0..7, 7..0, ...): order[p] is the head block at position p of a row, and position p runs on XCD p % 8.
-    for (int hy = tid; hy < plan.n_hy; hy += kScanThreads) {
-      const int mine = kept[hy / plan.HB];
+    __shared__ int32_t kept_h[256];  // kept rows per head block (at most 256 are ordered)
+    for (int hy = tid; hy < plan.n_hy && hy < 256; hy += kScanThreads) kept_h[hy] = kept[hy / plan.HB];
+    __syncthreads();
+    for (int hy = tid; hy < plan.n_hy && hy < 256; hy += kScanThreads) {
+      const int mine = kept_h[hy];
       int rank = 0;
       for (int o = 0; o < plan.n_hy; ++o) {
-        const int other = kept[o / plan.HB];
+        const int other = kept_h[o];
         rank += (other > mine) || (other == mine && o < hy);
       }
       const int round = rank >> 3, pos = rank & 7;

@@ -86,8 +86,8 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw, int n_hy,
     int n_split, const int32_t *__restrict__ chunk_tiles_dev, float qscale, int n_recent,
-    const int32_t *__restrict__ order, uint16_t *__restrict__ out, int out_token_major, float *__restrict__ part,
-    int32_t *__restrict__ tickets) {
+    const int32_t *__restrict__ order, int head_major, uint16_t *__restrict__ out, int out_token_major,
+    float *__restrict__ part, int32_t *__restrict__ tickets) {
   constexpr int QW = 4 / GB;   // query sub-tiles per workgroup
   constexpr int BM = 32 * QW;  // queries per workgroup
   constexpr int KS = D / 16;   // k-steps of S^T
@@ -104,16 +104,25 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   // workgroup id -> (query tile, chunk, unit/head block): heads vary fastest so that a head keeps its XCD
   const int n_qt = (L + BM - 1) / BM;
   const int per_qt = n_hy * n_split;
-  const int rem = blockIdx.x % per_qt;
+  int rem = blockIdx.x % per_qt;
   const int chunk = rem / n_hy;
-  const int qt_idx = blockIdx.x / per_qt;
+  int qt_idx = blockIdx.x / per_qt;
+  if (head_major) {
+    // Many heads: the resident workgroups should cover few of them, or a head's K/V rows leave the L2 between
+    // two of its query tiles and every tile comes from HBM again.  XCD x (workgroups x, x + 8, ...) walks heads
+    // x, x + 8, ... one after the other, each head's query tiles together, longest first.
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+    rem = (j / n_qt) * 8 + x;
+    qt_idx = j % n_qt;
+    if (rem >= n_hy) return;  // the grid is rounded up to whole groups of 8 heads
+  }
   const int qtile = n_qt - 1 - qt_idx;  // longest rows first
   // Position pos of a row goes to XCD pos % 8 and, inside it, to shader engine (pos / 8) % 4: both fixed for all
   // rows.  order[] gives each XCD its heads; rotating them over the XCD's positions from row to row lets every
   // shader engine see all of them, instead of one engine being stuck with the head that keeps most.
   const int pos = rem % n_hy;
   int hy = pos;
-  if (order) {
+  if (order && !head_major) {
     const int n_slot = n_hy >> 3;
     hy = order[(((pos >> 3) + qt_idx) % n_slot) * 8 + (pos & 7)];
   }
@@ -590,7 +599,10 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
     plan->chunk_tiles = ws.take<int32_t>(64);
     plan->tickets = ws.take<int32_t>((size_t)items);
   }
-  if (plan->n_hy % 8 == 0 && plan->n_hy >= 16 && plan->n_hy <= 1024) plan->order = ws.take<int32_t>(plan->n_hy);
+  // 16 or more heads per XCD: head-major block order (K/V reuse in the L2); fewer: a head order balanced by kept rows
+  plan->head_major = plan->n_split == 1 && plan->n_hy >= 128;
+  if (!plan->head_major && plan->n_hy % 8 == 0 && plan->n_hy >= 16 && plan->n_hy <= 256)
+    plan->order = ws.take<int32_t>(plan->n_hy);
   if (B * Hkv > 1024) {  // the planner holds the units' counts in LDS
     plan->order = nullptr;
     plan->chunk_tiles = nullptr;
@@ -610,12 +622,14 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
   const int G = Hq / Hkv;
   const int GB = G >= 4 ? 4 : G;
   if ((int64_t)plan.n_items * plan.n_split > 0x7fffffff) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)(plan.n_items * plan.n_split)), block(256);
+  const int n_qt = plan.n_items / plan.n_hy;
+  const int64_t blocks = plan.head_major ? (int64_t)((plan.n_hy + 7) / 8) * 8 * n_qt : (int64_t)plan.n_items * plan.n_split;
+  const dim3 grid((unsigned)blocks), block(256);
 #define AG_PF(GG, BB)                                                                                               \
   hipLaunchKernelGGL((ag_prefill_d128_kernel<GG, BB>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k,    \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
                      Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, n_recent, plan.order,               \
-                     (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)
+                     plan.head_major, (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)
   if (n_recent > 1) {
     if (GB == 1) AG_PF(1, true); else if (GB == 2) AG_PF(2, true); else AG_PF(4, true);
   } else {
