@@ -72,6 +72,7 @@ struct ag_pf_plan {
   int32_t *tickets;      // [n_items] chunks of an item that have stored their partial state
   int32_t *kept;         // [units]  kept rows per unit, exchanged between the scan's workgroups
   int n_hy, HB, BM, n_items, n_split, slots, max_tiles;
+  int NW;                // waves per workgroup of the prefill kernel (4 or 8)
   int head_major;        // block order of the prefill kernel: a head's query tiles together (many heads)
 };
 

@@ -80,15 +80,19 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 // BAND = the recent-token variant (Table 5): the evicted tokens among the n_recent - 1 tokens just before a query
 // stay visible to it.  They are read from the uncompacted K/V as up to three extra 64-key "band" tiles that run
 // through the same pipeline ahead of the compacted tiles of chunk 0, with their own mask.
-template <int GB, bool BAND>
-__global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
+// NW = waves per workgroup: 4 (two workgroups per CU).  (8, one workgroup per CU with twice the queries sharing
+// every K/V tile, also works without the band variant but is slower: the whole CU then moves in step.)
+template <int GB, bool BAND, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw, int n_hy,
     int n_split, const int32_t *__restrict__ chunk_tiles_dev, float qscale, int n_recent,
     const int32_t *__restrict__ order, int head_major, uint16_t *__restrict__ out, int out_token_major,
     float *__restrict__ part, int32_t *__restrict__ tickets) {
-  constexpr int QW = 4 / GB;   // query sub-tiles per workgroup
+  constexpr int QW = NW / GB;  // query sub-tiles per workgroup
+  constexpr int RPW = kBN / NW;  // tile rows each wave loads
+  constexpr int LI = RPW / 4;    // load instructions per wave and tile (4 rows each)
   constexpr int BM = 32 * QW;  // queries per workgroup
   constexpr int KS = D / 16;   // k-steps of S^T
   constexpr int DT = D / 32;   // 32-row tiles of O^T
@@ -193,17 +197,19 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   const __amdgpu_buffer_rsrc_t vb_rsrc =
       __builtin_amdgcn_make_buffer_rsrc((void *)(v + (size_t)u * L * D), 0, BAND ? L * kRowB : 0, 0x00020000);
   const int ld_r = lane >> 4;
-  int ld_off[4];
+  int ld_off[LI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    ld_off[i] = (16 * w4 + 4 * i + ld_r) * kRowB + (((lane & 15) ^ ((ld_r << 2) | i)) << 4);  // chunk (lane%16)^swz(r)
-  const uint32_t ld_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + w4 * 16 * kRowB;
+  for (int i = 0; i < LI; ++i) {
+    const int r = RPW * w4 + 4 * i + ld_r;
+    ld_off[i] = r * kRowB + (((lane & 15) ^ swz(r)) << 4);  // chunk (lane%16)^swz(r)
+  }
+  const uint32_t ld_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + w4 * RPW * kRowB;
   auto issue_k = [&](int i_step) {  // K of the tile of step i_step -> K buffer i_step & 1
     const bool bnd = BAND && i_step < n_band;
     const int soff = (bnd ? band_t0 + i_step : tile0 + i_step - n_band) * kTileB;
     const __amdgpu_buffer_rsrc_t rsrc = bnd ? kb_rsrc : k_rsrc;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LI; ++i) {
       const uint32_t dk = ld_base + (i_step & 1) * kTileB + i * 4 * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                    :: "s"(dk), "v"(ld_off[i]), "s"(rsrc), "s"(soff) : "memory");
@@ -214,7 +220,7 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
     const int soff = (bnd ? band_t0 + i_step : tile0 + i_step - n_band) * kTileB;
     const __amdgpu_buffer_rsrc_t rsrc = bnd ? vb_rsrc : v_rsrc;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LI; ++i) {
       const uint32_t dv = ld_base + 2 * kTileB + (i_step & 1) * kTileB + i * 4 * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                    :: "s"(dv), "v"(ld_off[i]), "s"(rsrc), "s"(soff) : "memory");
@@ -234,33 +240,45 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   uint2 vself[DT][4];
   {
     const int srow = lane >> 4, schunk = lane & 15;
-    u32x4 sq[2][4], sk[2][4], sv[2][4];
+    constexpr int RP = (kTileB / NW) / 256;  // rows per pass: the wave's corner of V1 holds RP rows of 256 bytes
+    constexpr int NP = 32 / RP;              // passes
+    constexpr int LP = RP / 4;               // whole-line loads per pass
+    u32x4 sq[NP][LP], sk[NP][LP], sv[NP][LP];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < NP; ++h)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = min(j0 + 16 * h + 4 * j + srow, L - 1);
+      for (int j = 0; j < LP; ++j) {
+        const int row = min(j0 + RP * h + 4 * j + srow, L - 1);
         // (all three unconditionally: the few workgroups that hold a later chunk of a split item do not use k, v)
         sq[h][j] = *reinterpret_cast<const u32x4 *>(q + ((size_t)(b * Hq + head) * L + row) * D + 8 * schunk);
         sk[h][j] = *reinterpret_cast<const u32x4 *>(k + ((size_t)u * L + row) * D + 8 * schunk);
         sv[h][j] = *reinterpret_cast<const u32x4 *>(v + ((size_t)u * L + row) * D + 8 * schunk);
       }
-    AG_LDS uint8_t *stage = (AG_LDS uint8_t *)smem + 3 * kTileB + w4 * 4096;
-    const int rr = col & 15;  // this lane's row inside a 16-row pass
-    auto put = [&](const u32x4 (&x)[4]) {
+    AG_LDS uint8_t *stage = (AG_LDS uint8_t *)smem + 3 * kTileB + w4 * (kTileB / NW);
+    const int rr = col % RP;  // this lane's row inside a pass
+    // lanes exchange data through the corner: a wave-level release/acquire pair on each side tells the compiler
+    // that one lane's store is another lane's load (the hardware keeps a wave's LDS accesses in order anyway)
+    auto wave_sync = [] {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto put = [&](const u32x4 (&x)[LP]) {
+      wave_sync();  // the previous contents have been read
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < LP; ++j) {
         const int r = 4 * j + srow;
         *reinterpret_cast<AG_LDS u32x4 *>(stage + r * 256 + ((schunk ^ r) << 4)) = x[j];
       }
+      wave_sync();  // the rows are there for every lane
     };
     auto get4 = [&](int off) {
       const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(stage + off);
       return make_uint4(x[0], x[1], x[2], x[3]);
     };
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const bool mine = (col >> 4) == h;
+    for (int h = 0; h < NP; ++h) {
+      const bool mine = (col / RP) == h;
       put(sq[h]);
       if (mine) {
 #pragma unroll
@@ -514,8 +532,8 @@ __global__ __launch_bounds__(256, 2) void ag_prefill_d128_kernel(
   // ---- an item cut into chunks: store this chunk's state; the chunk that arrives last merges and writes ----
   if (n_chunks > 1) {
     const size_t item = (size_t)qtile * n_hy + hy;
-    float *st = part + (item * n_split * 4 + w4) * (66 * 64) + lane;  // state of chunk c at st + c * cstride
-    const size_t cstride = (size_t)4 * 66 * 64;
+    float *st = part + (item * n_split * NW + w4) * (66 * 64) + lane;  // state of chunk c at st + c * cstride
+    const size_t cstride = (size_t)NW * 66 * 64;
     // The states travel through memory between workgroups of one launch.  They are written through and read
     // past the caches (system-scope relaxed accesses), so no cache-wide write-back or invalidate is needed: the
     // stores are complete (vmcnt 0) before the workgroup's arrival is counted, and the last arrival reads after it.
@@ -582,20 +600,21 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
   const int G = Hq / Hkv;
   const int GB = G >= 4 ? 4 : G;
   memset(plan, 0, sizeof(*plan));
-  plan->BM = 32 * (4 / GB);
+  plan->NW = 4;  // 8 waves (one workgroup per CU, twice the queries per K/V tile) measured 4-14 % slower
+  plan->BM = 32 * (plan->NW / GB);
   plan->HB = G / GB;
   plan->n_hy = B * Hkv * plan->HB;
   const int64_t items = (int64_t)((L + plan->BM - 1) / plan->BM) * plan->n_hy;
   plan->n_items = (int)items;
   plan->max_tiles = (L + kBN - 1) / kBN;
-  plan->slots = 2 * num_cu;
+  plan->slots = (8 / plan->NW) * num_cu;
   plan->n_split = 1;
   // (at most two chunks: the merge adds two rounded products, which is the same bit pattern in either order; more
   // chunks would need a fixed merge order to stay reproducible)
   if (items < (int64_t)8 * num_cu && plan->max_tiles > 16) plan->n_split = 2;
   *part = nullptr;
   if (plan->n_split > 1) {
-    *part = ws.take<float>((size_t)items * plan->n_split * 4 * 66 * 64);
+    *part = ws.take<float>((size_t)items * plan->n_split * plan->NW * 66 * 64);
     plan->chunk_tiles = ws.take<int32_t>(64);
     plan->tickets = ws.take<int32_t>((size_t)items);
   }
@@ -624,17 +643,19 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
   if ((int64_t)plan.n_items * plan.n_split > 0x7fffffff) return hipErrorInvalidValue;
   const int n_qt = plan.n_items / plan.n_hy;
   const int64_t blocks = plan.head_major ? (int64_t)((plan.n_hy + 7) / 8) * 8 * n_qt : (int64_t)plan.n_items * plan.n_split;
-  const dim3 grid((unsigned)blocks), block(256);
-#define AG_PF(GG, BB)                                                                                               \
-  hipLaunchKernelGGL((ag_prefill_d128_kernel<GG, BB>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k,    \
+  const dim3 grid((unsigned)blocks), block(64 * plan.NW);
+#define AG_PF(GG, BB) AG_PFN(GG, BB, 4)
+#define AG_PFN(GG, BB, NN)                                                                                          \
+  hipLaunchKernelGGL((ag_prefill_d128_kernel<GG, BB, NN>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k, \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
                      Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, n_recent, plan.order,               \
                      plan.head_major, (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)
   if (n_recent > 1) {
-    if (GB == 1) AG_PF(1, true); else if (GB == 2) AG_PF(2, true); else AG_PF(4, true);
+    if (GB == 1) { AG_PF(1, true); } else if (GB == 2) { AG_PF(2, true); } else { AG_PF(4, true); }
   } else {
-    if (GB == 1) AG_PF(1, false); else if (GB == 2) AG_PF(2, false); else AG_PF(4, false);
+    if (GB == 1) { AG_PF(1, false); } else if (GB == 2) { AG_PF(2, false); } else { AG_PF(4, false); }
   }
 #undef AG_PF
+#undef AG_PFN
   return hipGetLastError();
 }
