@@ -509,3 +509,55 @@ def test_gate_of_the_next_layer_overlaps_on_a_second_stream():
     for l in range(layers):
         assert torch.equal(f0[l], f1[l]) and torch.equal(o0[l], o1[l])
         assert torch.equal(c0[l].len, c1[l].len) and torch.equal(c0[l].k, c1[l].k)
+
+
+# ------------------------------------------------------------------------------------------- seeded shape sweeps
+def _sweep_cases(n, seed):
+    g = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(g.choice([64, 128, 128]))
+        dtype = "f32" if (i % 5 == 4) else "bf16"
+        G = int(g.choice([1, 1, 2, 4, 8]))
+        Hkv = int(g.integers(1, 5))
+        B = int(g.integers(1, 4))
+        L = int(g.choice([int(g.integers(1, 70)), int(g.integers(70, 400)), int(g.integers(400, 900))]))
+        if dtype == "f32":
+            L = min(L, 200)
+        keep = float(g.choice([0.0, 0.1, 0.5, 0.9, 1.0]))
+        n_recent = int(g.choice([1, 1, 3, 17]))
+        cases.append((dtype, B, Hkv * G, Hkv, L, D, keep, n_recent, bool(g.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(24, 170), ids=lambda c: "%s-B%d-Hq%d-Hkv%d-L%d-D%d-keep%.1f-w%d-%s" % (
+    c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[7], "cache" if c[8] else "nocache"))
+def test_prefill_shape_sweep(case):
+    """Seeded sweep over batch, group size, ragged lengths, keep ratios (incl. 0 and 1), window and both prefill
+    entry forms, element by element against the oracle."""
+    dtype, B, Hq, Hkv, L, D, keep, n_recent, with_cache = case
+    g = np.random.default_rng(171 + L + Hq)
+    q, k, v = (W.store(g.standard_normal(s).astype(np.float32), dtype)
+               for s in ((B, Hq, L, D), (B, Hkv, L, D), (B, Hkv, L, D)))
+    flags = (g.random((B, Hkv, L)) < keep).astype(np.uint8)
+    scale = 1.0 / math.sqrt(D)
+    got = host_f32(_prefill_recent(q, k, v, flags, scale, n_recent, with_cache))
+    ref = oracle.prefill_attn(q.f32, k.f32, v.f32, flags, scale, n_recent=n_recent)
+    err, tol = attn_error(dtype, got, ref), attn_tolerance(dtype, ref)
+    assert np.isfinite(got).all() and err <= tol, "err %.3g > tol %.3g" % (err, tol)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_shape_sweep(seed):
+    """Seeded sweep over ragged decode batches (group sizes, empty and one-row units, both dtypes and head sizes)."""
+    from test_parity_gpu import check_decode
+    g = np.random.default_rng(180 + seed)
+    dtype = "f32" if seed % 4 == 3 else "bf16"
+    D = int(g.choice([64, 128]))
+    G = int(g.choice([1, 2, 4, 8]))
+    Hkv, B = int(g.integers(1, 5)), int(g.integers(1, 4))
+    max_len = int(g.choice([40, 300, 1200]))
+    len0 = np.rint(max_len * g.random(B * Hkv)).astype(np.int32)
+    len0[g.integers(0, B * Hkv)] = 0
+    wl = W.decode_batch(40 + seed, "t", dtype, B, Hkv * G, Hkv, D, len0, 5, pos0=max_len + 1)
+    check_decode(wl, 5, 0.5, dtype)
