@@ -11,15 +11,25 @@
 
 namespace {
 
-constexpr int kChunk = 256;      // rows per work item
+constexpr int kChunk = 128;      // rows per work item
+constexpr int kWgsPerCu = 2;     // persistent workgroups per CU (measured on 1024 ragged caches: 2 -> 5.7 TB/s,
+                                 // 3 -> 5.3, 4 -> 5.4, 1 -> 4.6; fewer concurrent streams keep DRAM pages open)
 constexpr int kMaxUnits = 8192;  // units whose item offsets fit in LDS
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <typename T> struct elems;  // element count and widening of one 16-byte vector
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+template <typename T> struct elems;  // element count, widening and dot product of one 16-byte vector
 template <> struct elems<float> {
   static constexpr int n = 4;
   static __device__ __forceinline__ void widen(const uint4 &r, float *f) {
     f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+  static __device__ __forceinline__ float dot(const uint4 &a, const uint4 &b) {
+    float d = __uint_as_float(a.x) * __uint_as_float(b.x);
+    d = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), d);
+    d = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), d);
+    return fmaf(__uint_as_float(a.w), __uint_as_float(b.w), d);
   }
 };
 template <> struct elems<uint16_t> {  // bf16 bit patterns
@@ -29,6 +39,13 @@ template <> struct elems<uint16_t> {  // bf16 bit patterns
     f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
     f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
     f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+  // 8 bf16 products summed in fp32 by v_dot2c_f32_bf16, two per instruction, without widening either operand
+  static __device__ __forceinline__ float dot(const uint4 &a, const uint4 &b) {
+    float d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.x), __builtin_bit_cast(bf16x2, b.x), 0.f, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.y), __builtin_bit_cast(bf16x2, b.y), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.z), __builtin_bit_cast(bf16x2, b.z), d, false);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.w), __builtin_bit_cast(bf16x2, b.w), d, false);
   }
 };
 
@@ -70,25 +87,36 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
                                                                 const T *__restrict__ vc,
                                                                 const int64_t *__restrict__ row_off,
                                                                 const int32_t *__restrict__ len, int U, int Hkv,
-                                                                float qscale, int32_t *__restrict__ item_off_g,
+                                                                int meta_lds, float qscale,
+                                                                int32_t *__restrict__ item_off_g,
                                                                 float *__restrict__ pm, float *__restrict__ pl,
                                                                 float *__restrict__ pacc) {
   constexpr int EPL = elems<T>::n;        // elements per lane
   constexpr int LPR = D / EPL;            // lanes per row
   constexpr int GPW = 64 / LPR;           // rows per wave load
   constexpr int NST = 4 * GPW;            // online-softmax states per block
-  constexpr int UN = G <= 2 ? 8 : 4;      // rows in flight per lane group
+  constexpr int NIT = kChunk / 4 / GPW;   // loads that cover a wave's quarter of an item
+  constexpr int UN = (G <= 2 ? 8 : 4) < NIT ? (G <= 2 ? 8 : 4) : NIT;  // rows in flight per lane group
+  static_assert(NIT % UN == 0, "a wave's rows must be a whole number of batches");
   extern __shared__ int32_t smem[];
   int32_t *item_off = smem;               // [U+1]
   int32_t *scan = smem + (U + 1);         // [256]
   float *st = reinterpret_cast<float *>(scan + 256);  // [NST][G][D+2]
+  // with few enough units their lengths and slab offsets also live in LDS, so that starting an item costs no
+  // round trip to memory
+  int32_t *s_len = reinterpret_cast<int32_t *>(st + (size_t)NST * G * (D + 2));  // [U]     (meta_lds)
+  int64_t *s_ro = reinterpret_cast<int64_t *>((reinterpret_cast<uintptr_t>(s_len + U) + 7) & ~uintptr_t(7));  // [U]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   // ---- item offsets: exclusive scan of ceil(len/kChunk) over units ----
   const int per = (U + 255) / 256;
   const int u0 = tid * per, u1 = min(U, u0 + per);
   int32_t sum = 0;
-  for (int u = u0; u < u1; ++u) sum += (unit_len(len, row_off, u) + kChunk - 1) / kChunk;
+  for (int u = u0; u < u1; ++u) {
+    const int n_u = unit_len(len, row_off, u);
+    if (meta_lds) { s_len[u] = n_u; s_ro[u] = row_off[u]; }
+    sum += (n_u + kChunk - 1) / kChunk;
+  }
   scan[tid] = sum;
   __syncthreads();
   for (int d = 1; d < 256; d <<= 1) {
@@ -119,20 +147,16 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
     const int u = lo;
     const int c = item - item_off[u];
     const int b = u / Hkv, g = u - b * Hkv;
-    const int n = unit_len(len, row_off, u);
+    const int n = meta_lds ? s_len[u] : unit_len(len, row_off, u);
+    const int64_t ro = meta_lds ? s_ro[u] : row_off[u];
     const int row_end = min(n, (c + 1) * kChunk);
     const int wrow0 = c * kChunk + wave * (kChunk / 4);
-    const uint4 *K = reinterpret_cast<const uint4 *>(kc + (size_t)row_off[u] * D);
-    const uint4 *V = reinterpret_cast<const uint4 *>(vc + (size_t)row_off[u] * D);
+    const uint4 *K = reinterpret_cast<const uint4 *>(kc + (size_t)ro * D);
+    const uint4 *V = reinterpret_cast<const uint4 *>(vc + (size_t)ro * D);
 
-    float qf[G][EPL];
+    uint4 qr[G];  // this lane's 16 bytes of each query row, as stored; the score is scaled after the sum
 #pragma unroll
-    for (int gg = 0; gg < G; ++gg) {
-      const uint4 r = reinterpret_cast<const uint4 *>(q + ((size_t)(b * Hkv + g) * G + gg) * D)[seg];
-      elems<T>::widen(r, qf[gg]);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) qf[gg][e] *= qscale;
-    }
+    for (int gg = 0; gg < G; ++gg) qr[gg] = reinterpret_cast<const uint4 *>(q + ((size_t)(b * Hkv + g) * G + gg) * D)[seg];
     float m[G], l[G], acc[G][EPL];
 #pragma unroll
     for (int gg = 0; gg < G; ++gg) {
@@ -141,7 +165,7 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
       for (int e = 0; e < EPL; ++e) acc[gg][e] = 0.f;
     }
 
-    for (int it0 = 0; it0 < kChunk / 4 / GPW; it0 += UN) {
+    for (int it0 = 0; it0 < NIT; it0 += UN) {
       if (wrow0 + it0 * GPW >= row_end) break;  // wave-uniform
       uint4 kk[UN], vv[UN];
       bool ok[UN];
@@ -159,14 +183,9 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
       float s[G][UN];
 #pragma unroll
       for (int j = 0; j < UN; ++j) {
-        float kf[EPL];
-        elems<T>::widen(kk[j], kf);
 #pragma unroll
         for (int gg = 0; gg < G; ++gg) {
-          float d = 0.f;
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) d = fmaf(qf[gg][e], kf[e], d);
-          d = group_sum<LPR>(d);
+          const float d = group_sum<LPR>(elems<T>::dot(qr[gg], kk[j])) * qscale;
           s[gg][j] = ok[j] ? d : -INFINITY;
         }
       }
@@ -392,9 +411,11 @@ hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new
   float *pacc = ws.take<float>(items * G * D);
   if (!ws.ok) return hipSuccess;
   constexpr int EPL = elems<T>::n, LPR = D / EPL, GPW = 64 / LPR, NST = 4 * GPW;
-  const size_t shmem = (size_t)(U + 1 + 256) * 4 + (size_t)NST * G * (D + 2) * 4;
+  const int meta_lds = U <= 2048;
+  const size_t shmem = (size_t)(U + 1 + 256) * 4 + (size_t)NST * G * (D + 2) * 4 +
+                       (meta_lds ? (size_t)U * 4 + 8 + (size_t)U * 8 : 0);
   const float qscale = scale * kLog2e;
-  int blocks = num_cu * 4;
+  int blocks = num_cu * kWgsPerCu;
   if (blocks > items) blocks = (int)items;
   if (blocks < 1) blocks = 1;
   if (shmem > 48 * 1024) {
@@ -404,7 +425,7 @@ hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new
   }
   ag_tick(ctx, AG_K_DECODE_PARTIAL, s);
   hipLaunchKernelGGL((ag_decode_partial_kernel<T, D, G>), dim3(blocks), dim3(256), shmem, s, (const T *)q,
-                     (const T *)kc, (const T *)vc, row_off, len, U, Hkv, qscale, item_off, pm, pl, pacc);
+                     (const T *)kc, (const T *)vc, row_off, len, U, Hkv, meta_lds, qscale, item_off, pm, pl, pacc);
   ag_tock(ctx, AG_K_DECODE_PARTIAL, s);
   ag_tick(ctx, AG_K_DECODE_MERGE, s);
   hipLaunchKernelGGL((ag_decode_merge_kernel<T, D>), dim3(B * Hq), dim3(D), 0, s, (const T *)q, (const T *)k_new,
