@@ -57,6 +57,8 @@ ag_status need_device(ag_ctx *ctx) {
 
 }  // namespace
 
+constexpr size_t kTailBytes = 256 + kGateTickets * sizeof(int32_t);
+
 extern "C" {
 
 ag_status ag_create(ag_ctx **out, int device, size_t workspace_bytes) {
@@ -74,11 +76,12 @@ ag_status ag_create(ag_ctx **out, int device, size_t workspace_bytes) {
     if (e == hipSuccess) {
       ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
       ctx->ws_bytes = ag_align256(workspace_bytes);
-      e = hipMalloc((void **)&ctx->ws, ctx->ws_bytes + 256);
+      e = hipMalloc((void **)&ctx->ws, ctx->ws_bytes + kTailBytes);
     }
-    if (e == hipSuccess) {
+    if (e == hipSuccess) {  // behind the workspace: the error word and the gate's arrival counters, all zero
       ctx->d_err = reinterpret_cast<int32_t *>(ctx->ws + ctx->ws_bytes);
-      e = hipMemset(ctx->d_err, 0, 256);
+      ctx->gate_tickets = reinterpret_cast<int32_t *>(ctx->ws + ctx->ws_bytes + 256);
+      e = hipMemset(ctx->d_err, 0, kTailBytes);
     }
     if (e != hipSuccess) {
       if (ctx->ws) (void)hipFree(ctx->ws);

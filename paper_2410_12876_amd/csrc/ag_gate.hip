@@ -3,8 +3,8 @@
 // The product is a skinny GEMM (N = H_f <= 32) whose cost is reading the features once from HBM.  The bf16
 // path runs it on MFMA (v_mfma_f32_32x32x16_bf16, N padded to 32): every wave owns MT x 32 tokens and a slice
 // of the K range, streams its feature rows with 16-byte loads that together cover whole 128-byte lines, and
-// takes the matching W fragments from a pre-packed copy that stays in L2.  K is split over the 4 waves of a
-// workgroup.  With enough tokens one fused kernel does everything (ag_gate_fused_kernel).  With few tokens K is
+// takes the matching W fragments either from W as stored, transposed on the way through LDS (fused kernel), or
+// from a pre-packed copy that stays in L2.  K is split over the waves of a workgroup.  With enough tokens one fused kernel does everything (ag_gate_fused_kernel).  With few tokens K is
 // also split over several workgroups; partial sums then go to the workspace and a second kernel adds them in a
 // fixed order (so flags are reproducible run to run), adds the bias, compares with the logit-space threshold and
 // writes the flags head-major.
@@ -13,16 +13,17 @@
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+#define AG_LDS __attribute__((address_space(3)))
 
 constexpr int kNP = 32;  // padded head count (MFMA N)
 
 // W [d_in, H_f] bf16 -> fragment order: [(chunk*4 + step)*64 + lane][8], lane = (n = lane%32, kb = lane/32),
 // element j = W[chunk*64 + kb*32 + step*8 + j][n]  (0 for n >= H_f).
-__global__ void ag_gate_pack_w(const uint16_t *__restrict__ w, int d_in, int H_f, uint16_t *__restrict__ wp,
-                               int32_t *__restrict__ tickets, int n_tickets) {
+__global__ void ag_gate_pack_w(const uint16_t *__restrict__ w, int d_in, int H_f, uint16_t *__restrict__ wp) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;  // one packed element
-  if (i < n_tickets) tickets[i] = 0;  // arrival counters of the fused kernel's K splits
   if (i >= d_in * kNP) return;
   const int j = i & 7, lane = (i >> 3) & 63, step = (i >> 9) & 3, chunk = i >> 11;
   const int n = lane & 31, kb = lane >> 5;
@@ -89,12 +90,22 @@ __global__ __launch_bounds__(256) void ag_gate_mfma_kernel(const uint16_t *__res
 // goes on to bias, threshold, logits and head-major flags.  With several, each stores its 32x32 partial tile
 // (written through the caches, complete before its arrival is counted) and the split that arrives last adds all
 // of them in split order -- the same order whoever is last, so the flags are reproducible -- and finishes.
+// The arrival counters live in the context, start at zero and are set back to zero by the split that arrives
+// last, so no launch has to clear them.
+//
+// RAW: W is taken as the caller stores it ([d_in, H_f] row-major, H_f a multiple of 4, 16-byte aligned).  A wave
+// copies the 64 rows of a chunk into its own 4 KiB of LDS and reads them back with the transposing LDS read,
+// which hands lane (n, kb) the eight rows kb*32 + step*8 + 0..7 of column n: the B operand that matches the
+// A operand's 16-byte feature loads.  Columns n >= H_f read whatever follows in LDS; they only reach output
+// columns that are never stored.  Otherwise wp holds the fragments prepared by ag_gate_pack_w.
 constexpr int kFusedWaves = 8;
+template <bool RAW>
 __global__ __launch_bounds__(64 * kFusedWaves) void ag_gate_fused_kernel(
     const uint16_t *__restrict__ x, const uint4 *__restrict__ wp, int64_t tokens, int d_in, int L, int H_f,
     const float *__restrict__ bias, float thr, int n_sink, float *__restrict__ logits, uint8_t *__restrict__ flags,
     float *__restrict__ partial, int32_t *__restrict__ tickets) {
-  __shared__ float red[kFusedWaves][32][33];
+  // [wave][4 KiB]: W staging of the wave while it accumulates, afterwards its 32 x 32 fp32 partial tile
+  __shared__ __attribute__((aligned(16))) uint8_t wst[kFusedWaves][4096];
   __shared__ uint8_t fl[kNP][32];
   __shared__ int is_last;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -106,20 +117,62 @@ __global__ __launch_bounds__(64 * kFusedWaves) void ag_gate_fused_kernel(
   int64_t tok = tok0 + m;
   if (tok >= tokens) tok = tokens - 1;  // clamp: the row is read but its result is never written
   const uint4 *row = reinterpret_cast<const uint4 *>(x + (size_t)tok * d_in + kb * 32);
+  // RAW: a chunk is 64 * H_f * 2 bytes = 8 * H_f uint4, lane l holds uint4 l, l + 64, ... of it
+  const int chunk_u4 = 8 * H_f;
+  AG_LDS uint8_t *stage = (AG_LDS uint8_t *)wst[wave];
+  // transposing read: the 16 lanes of a group give the addresses of 4 rows x 16 columns (lane i: row i / 4,
+  // columns 4 (i % 4) ..+3) and lane i receives column i of the 4 rows
+  const int gl = lane >> 4, li = lane & 15;
+  const int tr_col = min(16 * (gl & 1) + 4 * (li & 3), H_f - 4);
+  const int tr_off = ((gl >> 1) * 32 + (li >> 2)) * (H_f * 2) + tr_col * 2;
+  auto wave_sync = [] {  // lanes of one wave exchange data through LDS
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
   constexpr int PF = 4;
   for (int c0 = c_lo + wave; c0 < c_hi; c0 += kFusedWaves * PF) {
     uint4 a[PF][4], b[PF][4];
+    // W first: its loads hit the L2 and return early, so the staging below runs while the feature rows are
+    // still on their way from HBM (a wave's loads return in issue order)
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
-      const int c = c0 + kFusedWaves * p;
-      if (c < c_hi) {
+      const int c = min(c0 + kFusedWaves * p, c_hi - 1);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) a[p][s] = row[c * 8 + s];
+      for (int s = 0; s < 4; ++s) {
+        if (RAW) {
+          const int i = min(s * 64 + lane, chunk_u4 - 1);
+          b[p][s] = wp[(size_t)c * chunk_u4 + i];
+        } else {
+          b[p][s] = wp[((size_t)c * 4 + s) * 64 + lane];
+        }
+      }
+    }
 #pragma unroll
-        for (int s = 0; s < 4; ++s) b[p][s] = wp[((size_t)c * 4 + s) * 64 + lane];
+    for (int p = 0; p < PF; ++p) {
+      const int c = min(c0 + kFusedWaves * p, c_hi - 1);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) a[p][s] = row[c * 8 + s];
+    }
+    if (RAW) {
+#pragma unroll
+      for (int p = 0; p < PF; ++p) {
+        wave_sync();  // the fragments of the previous chunk have been read
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          if (s * 64 + lane < chunk_u4)
+            *reinterpret_cast<AG_LDS u32x4 *>(stage + (s * 64 + lane) * 16) =
+                u32x4{b[p][s].x, b[p][s].y, b[p][s].z, b[p][s].w};
+        wave_sync();  // the chunk's rows are there for every lane
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((AG_LDS bf16x4 *)(stage + tr_off + (s * 8) * (H_f * 2)));
+          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((AG_LDS bf16x4 *)(stage + tr_off + (s * 8 + 4) * (H_f * 2)));
+          b[p][s] = __builtin_bit_cast(uint4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
       }
     }
 #pragma unroll
@@ -131,6 +184,8 @@ __global__ __launch_bounds__(64 * kFusedWaves) void ag_gate_fused_kernel(
                                                         __builtin_bit_cast(bf16x8, b[p][s]), acc, 0, 0, 0);
       }
   }
+  float(*red)[32][32] = reinterpret_cast<float(*)[32][32]>(wst);
+  if (RAW) wave_sync();  // the wave's staging area becomes its partial tile
 #pragma unroll
   for (int r = 0; r < 16; ++r) red[wave][8 * (r >> 2) + 4 * kb + (r & 3)][m] = acc[r];
   __syncthreads();
@@ -155,6 +210,7 @@ __global__ __launch_bounds__(64 * kFusedWaves) void ag_gate_fused_kernel(
       is_last = __hip_atomic_fetch_add(&tickets[blockIdx.x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
     __syncthreads();
     if (!is_last) return;
+    if (threadIdx.x == 0) tickets[blockIdx.x] = 0;  // ready for the next launch
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       float sum = 0.f;
@@ -278,8 +334,7 @@ size_t ag_ws_gate_bytes(int64_t tokens, int d_in, int H_f, ag_dtype dt) {
   const int64_t tokens_pad = (tokens + 63) / 64 * 64;
   const size_t part = ag_align256((size_t)16 * tokens_pad * kNP * sizeof(float));
   const size_t pack = dt == AG_BF16 ? ag_align256((size_t)d_in * kNP * 2) : 0;
-  const size_t tickets = ag_align256((size_t)(tokens / 32 + 1) * sizeof(int32_t));  // fused kernel's K splits
-  return part + pack + tickets;
+  return part + pack;
 }
 
 hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype dt, int B, int L, int d_in,
@@ -291,22 +346,31 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
   const bool fused = dt == AG_BF16 && tiles32 >= ctx->num_cu / 4;  // enough token tiles: one fused kernel
   int fsplits = 1;
   if (fused) {  // K splits until the chip is covered, each wave keeping at least 2 chunks
-    while (tiles32 * fsplits < ctx->num_cu && d_in / 64 / (fsplits * 2) >= 2 * kFusedWaves && fsplits < 8) fsplits *= 2;
+    while (tiles32 * fsplits < ctx->num_cu && d_in / 64 / (fsplits * 2) >= 2 * kFusedWaves && fsplits < 8 &&
+           tiles32 <= kGateTickets)
+      fsplits *= 2;
   }
+  // the fused kernel reads W as stored when its rows can be moved and transposed in 8- and 16-byte pieces
+  const bool raw_w = fused && H_f % 4 == 0 && (reinterpret_cast<uintptr_t>(w) & 15) == 0;
   float *partial = fused ? (fsplits > 1 ? ws.take<float>((size_t)tiles32 * fsplits * 1024) : nullptr)
                          : ws.take<float>((size_t)p.splits * p.tokens_pad * kNP);
-  int32_t *tickets = fused && fsplits > 1 ? ws.take<int32_t>((size_t)tiles32) : nullptr;
-  uint16_t *wp = dt == AG_BF16 ? ws.take<uint16_t>((size_t)d_in * kNP) : nullptr;
+  int32_t *tickets = fused && fsplits > 1 ? ctx->gate_tickets : nullptr;
+  uint16_t *wp = dt == AG_BF16 && !raw_w ? ws.take<uint16_t>((size_t)d_in * kNP) : nullptr;
   if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
   if (dt == AG_BF16) {
-    const int n = d_in * kNP;
-    hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp,
-                       tickets, tickets ? (int)tiles32 : 0);
+    if (!raw_w) {
+      const int n = d_in * kNP;
+      hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp);
+    }
     if (fused) {
+      const dim3 grid((unsigned)tiles32, fsplits), block(64 * kFusedWaves);
       ag_tick(ctx, AG_K_GATE, s);
-      hipLaunchKernelGGL(ag_gate_fused_kernel, dim3((unsigned)tiles32, fsplits), dim3(64 * kFusedWaves), 0, s,
-                         (const uint16_t *)feat, (const uint4 *)wp, tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags,
-                         partial, tickets);
+      if (raw_w)
+        hipLaunchKernelGGL(ag_gate_fused_kernel<true>, grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)w,
+                           tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags, partial, tickets);
+      else
+        hipLaunchKernelGGL(ag_gate_fused_kernel<false>, grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)wp,
+                           tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags, partial, tickets);
       ag_tock(ctx, AG_K_GATE, s);
       return hipGetLastError();
     }

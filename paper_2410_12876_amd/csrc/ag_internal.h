@@ -10,6 +10,7 @@
 enum { AG_K_GATE = 0, AG_K_GATE_FINALIZE, AG_K_FLAG_SCAN, AG_K_COMPACT, AG_K_PREFILL, AG_K_DECODE_PARTIAL,
        AG_K_DECODE_MERGE, AG_K_MHA_PROJ, AG_K_MHA_ATTN, AG_K_COUNT };
 constexpr int kTimerSlots = 1024;  // launches remembered per kernel id
+constexpr int kGateTickets = 1024; // token tiles whose K splits can be counted
 
 struct ag_timer {
   hipEvent_t *start, *stop;  // kTimerSlots each, created on first enable
@@ -22,6 +23,7 @@ struct ag_ctx {
   char *ws;         // device workspace
   size_t ws_bytes;
   int32_t *d_err;   // sticky device error word (bit 0: cache capacity overflow)
+  int32_t *gate_tickets;  // [kGateTickets] arrival counters of the gate's K splits: zero between launches
   bool timing;
   ag_timer timers[AG_K_COUNT];
   char err[320];
