@@ -47,6 +47,17 @@ typedef enum {
 typedef enum { AG_F32 = 0, AG_BF16 = 1 } ag_dtype;
 
 /*
+ * Gate settings of the paper's two experiments: threshold tau of Eq. 4 and the constant gamma that
+ * Sec. 3.5 ("Initialization") adds inside the sigmoid.  gamma enters ag_gate as a bias of gamma in every head.
+ * Continual pre-training (Sec. 4.1, training details): tau = 0.5, gamma = 2.
+ * Supervised fine-tuning (Sec. 4.2, implementation details): tau = 0.3, gamma = 0.
+ */
+#define AG_TAU_PRETRAIN 0.5f
+#define AG_GAMMA_PRETRAIN 2.0f
+#define AG_TAU_FINETUNE 0.3f
+#define AG_GAMMA_FINETUNE 0.0f
+
+/*
  * Ragged per-(batch, KV head) cache.  Unit u = b * Hkv + g owns rows [row_off[u], row_off[u+1]) of k, v and
  * idx; its first len[u] rows are valid, in increasing token position.  All pointers are device memory.
  */

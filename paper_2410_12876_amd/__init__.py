@@ -16,6 +16,10 @@ LIB_PATH = os.path.join(_HERE, "libag.so")
 
 AG_OK, AG_EINVAL, AG_EUNSUPPORTED, AG_ECAPACITY, AG_EWORKSPACE, AG_EHIP = range(6)
 AG_F32, AG_BF16 = 0, 1
+# (tau, gamma) of the paper's two experiments (Sec. 4.1 training details; Sec. 4.2 implementation details); gamma is
+# the constant of Sec. 3.5 inside the sigmoid and enters ag_gate as a bias of gamma in every head
+PRESET_PRETRAIN = (0.5, 2.0)
+PRESET_FINETUNE = (0.3, 0.0)
 STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWORKSPACE", "AG_EHIP"]
 
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",

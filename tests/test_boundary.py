@@ -108,3 +108,11 @@ def test_missing_library_fails_loudly(monkeypatch, lib):
     monkeypatch.setattr(ag, "LIB_PATH", "/nonexistent/libag.so")
     with pytest.raises(ImportError):
         ag.load()
+
+
+def test_gate_presets_match_the_header():
+    """(tau, gamma) of the two experiments (Sec. 4.1 training details, Sec. 4.2 implementation details)."""
+    text = open(os.path.join(ROOT, "include", "ag.h")).read()
+    val = {m.group(1): float(m.group(2)) for m in re.finditer(r"#define (AG_(?:TAU|GAMMA)_[A-Z]+) ([0-9.]+)f", text)}
+    assert (val["AG_TAU_PRETRAIN"], val["AG_GAMMA_PRETRAIN"]) == ag.PRESET_PRETRAIN == (0.5, 2.0)
+    assert (val["AG_TAU_FINETUNE"], val["AG_GAMMA_FINETUNE"]) == ag.PRESET_FINETUNE == (0.3, 0.0)

@@ -287,6 +287,21 @@ def test_gate_threshold_is_strict_and_tau_half_means_positive_logit():
     assert flags[0, 0].tolist() == [1, 1, 0, 1, 1]
 
 
+@pytest.mark.parametrize("tau,gamma", [(0.5, 2.0), (0.3, 0.0)])
+def test_gate_with_the_papers_settings_in_probability_space(tau, gamma):
+    """Sec. 4.1 / Sec. 4.2 settings: flag = Sigmoid(s + gamma) > tau (Eq. 4 with the constant of Sec. 3.5), gamma
+    passed as a bias of gamma in every head."""
+    B, L, d, H = 1, 200, 16, 4
+    x, w = rnd(61, B, L, d), rnd(62, d, H)
+    _, flags = oracle.gate(x, w, np.full(H, gamma, np.float32), tau)
+    s = x.astype(np.float64) @ w.astype(np.float64)
+    sig = 1.0 / (1.0 + np.exp(-(s + gamma)))
+    far = np.abs(sig - tau) > 1e-9
+    assert np.array_equal(flags.transpose(0, 2, 1).astype(bool)[far], (sig > tau)[far])
+    if gamma > 0:  # the constant pushes the retention up
+        assert flags.mean() > oracle.gate(x, w, np.zeros(H, np.float32), tau)[1].mean()
+
+
 def test_gate_flag_layout_is_head_major():
     B, L, d, H = 2, 6, 3, 4
     x = rnd(35, B, L, d)
