@@ -215,6 +215,85 @@ def decode_leg(args, torch, ag, W):
     return res, wl
 
 
+def decode_stack_leg(args, torch, ag, W):
+    """Config 5's decode phase: one token through 32 layers = 32 ag_decode_attn calls on 32 ragged caches
+    (B = 16, 32 heads x 128; kept rows per layer from config5_decode_lens), eager and replayed from a HIP graph.
+    Cache contents are seeded N(0,1) drawn on the device (their values do not change the traffic)."""
+    layers, B, H, D, steps = 32, 16, 32, 128, args.stack_steps
+    U = B * H
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    caches, rows = [], 0
+    for l in range(layers):
+        len0 = W.config5_decode_lens(l, B)
+        cap = len0.astype(np.int64) + steps + 16
+        ro = np.zeros(U + 1, dtype=np.int64)
+        np.cumsum(cap, out=ro[1:])
+        total = int(ro[-1])
+        k = torch.randn(total, D, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+        v = torch.randn(total, D, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+        caches.append(ag.KVCache(k, v, torch.zeros(total, dtype=torch.int32, device="cuda"), torch.from_numpy(ro).cuda(),
+                                 torch.from_numpy(len0).cuda(), B, H, D, total_rows=total))
+        rows = max(rows, total)
+    ctx = ag.Context(0, ag.workspace_bytes(B, 1, H, H, D, ag.AG_BF16, 0, rows))
+    q, kn, vn = (torch.randn(B, H, D, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
+    outs = [torch.empty(B, H, D, dtype=torch.bfloat16, device="cuda") for _ in range(layers)]
+    scale = 1.0 / math.sqrt(D)
+
+    def token():
+        for l in range(layers):
+            ag.ag_decode_attn(ctx, q, kn, vn, None, 2048, scale, caches[l], outs[l])
+
+    def lens():
+        return torch.stack([c.len for c in caches]).clone()
+
+    def set_lens(x):
+        for l, c in enumerate(caches):
+            c.len.copy_(x[l])
+
+    token()
+    torch.cuda.synchronize()
+    # graph of one token; replays checked against the eager token from the same lengths
+    start = lens()
+    token()
+    torch.cuda.synchronize()
+    ref = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    set_lens(start)
+    with torch.cuda.graph(graph, stream=side):
+        token()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(3):
+        set_lens(start)
+        for o in outs:
+            o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        if not all(torch.equal(a, b) for a, b in zip(outs, ref)):
+            raise RuntimeError("decode graph replay %d differs from the eager token" % r)
+        token()  # eager work between replays
+        torch.cuda.synchronize()
+    res = {}
+    for name, run in (("eager", token), ("graph", graph.replay)):
+        set_lens(start)
+        torch.cuda.synchronize()
+        before = int(lens().sum())
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        after = int(lens().sum())
+        byts = 0.5 * (before + after) * D * 2 * 2
+        res[name] = {"ms_per_token": dt / steps * 1e3, "gbs": byts * steps / dt / 1e9}
+    ctx.poll_error()
+    ctx.close()
+    return {"workload": "cfg5_decode_32_layers_B16", "tokens": steps, "launches_per_token": 2 * layers,
+            "bytes_per_token": byts, **{k + "_" + kk: vv for k, v in res.items() for kk, vv in v.items()}}
+
+
 def overlap_leg(args, torch, ag, W, wl):
     """Several layers back to back: the gate of layer l+1 takes its input from before layer l's attention
     (previous-layer gating, Table 3), so it can run on a second stream (own context and workspace) beside layer
@@ -343,6 +422,9 @@ def main():
                     help="one keep ratio for every head instead of config 2's per-head U[0.2, 0.9]")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-batch", type=int, default=32)
+    ap.add_argument("--decode-stack", action="store_true",
+                    help="also time config 5's decode phase (one token through 32 layers, eager and from a HIP graph)")
+    ap.add_argument("--stack-steps", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching it eagerly")
     ap.add_argument("--skip-decode", action="store_true")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
@@ -379,6 +461,10 @@ def main():
         log("[bench] timing the CPU oracle on one step ...")
         cpu = cpu_baseline(wl, W)
     overlap = None if args.skip_overlap else overlap_leg(args, torch, ag, W, wl)
+    stack = None
+    if args.decode_stack:
+        log("[bench] config 5 decode phase, 32 layers ...")
+        stack = decode_stack_leg(args, torch, ag, W)
     machine = None if args.skip_machine else machine_context(torch, ag)
     if machine:
         pre["roofline"]["frac_of_vendor_gemm"] = pre["roofline"]["achieved"] / machine["vendor_gemm_bf16_8192_tflops"]
@@ -392,7 +478,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": pre["config"], "kernel_ms": pre["kernel_ms"], "roofline": pre["roofline"],
         "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
-        "next_layer_gate_overlap": overlap, "machine": machine,
+        "next_layer_gate_overlap": overlap, "decode_stack": stack, "machine": machine,
     }
     print(json.dumps(line))
 

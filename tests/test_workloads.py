@@ -47,3 +47,15 @@ def test_decode_batch_structure():
         assert (np.diff(ix) > 0).all() and (ix >= 0).all() and (ix < 256).all()
     q, kn, vn, nf = wl.step_inputs(0)
     assert q.bits.shape == (2, 32, 128) and nf.shape == (2, 32)
+
+
+def test_config5_decode_lens_follow_the_layer_keep_ratios():
+    for layer in (0, 16, 31):
+        lens = W.config5_decode_lens(layer).reshape(16, 32)
+        rho = 0.9 - 0.8 * layer / 31
+        live = lens[:, lens[0] > 0]
+        assert abs(live.mean() / 2048 - rho) < 0.04
+        assert lens.min() >= 0 and lens.max() <= 2048
+        assert np.array_equal(W.config5_decode_lens(layer), lens.reshape(-1))   # seeded
+    dead = (W.config5_decode_lens(31).reshape(16, 32) == 0).all(0)
+    assert dead.sum() >= 1   # fully evicted heads in the deepest layer, the same heads for every sequence

@@ -287,6 +287,22 @@ def decode_batch(config: int, name: str, dtype: str, B: int, Hq: int, Hkv: int, 
                           store(k, dtype), store(v, dtype), idx, pos0)
 
 
+def config5_decode_lens(layer: int, B: int = 16, L: int = 2048, n_layers: int = 32) -> np.ndarray:
+    """Kept rows per (batch, head) unit of layer `layer` after a 2048-token prompt, for the 32-layer decode
+    phase: the layer's per-head keep ratios are those of config5_layer (fully evicted heads included), each
+    sequence of the batch deviates from them by a few rows."""
+    H = 32
+    g = rng(5, 1000 + layer)
+    rho = 0.9 - 0.8 * layer / (n_layers - 1)
+    keep = np.clip(rho + 0.05 * (g.random(H) - 0.5), 0.02, 0.98)
+    dead = (g.random(H) < 0.10) if layer >= 24 else np.zeros(H, dtype=bool)
+    gb = rng(5, 5000 + layer)
+    lens = np.rint(keep[None, :] * L + 8.0 * gb.standard_normal((B, H)))
+    lens = np.clip(lens, 1, L)
+    lens[:, dead] = 0
+    return lens.astype(np.int32).reshape(B * H)
+
+
 def config3(B: int = 32, steps: int = 256, max_len: int = 4096) -> DecodeWorkload:
     """Decode-heavy batch: 32 heads x 128, len ~ round(max_len * U[0.1, 1]), 5 % of units len 1."""
     H, D = 32, 128
