@@ -263,16 +263,39 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
                                                             int32_t *__restrict__ len, T *__restrict__ out,
                                                             int32_t *__restrict__ d_err, ag_ring_dev ring) {
   __shared__ float red[D / 64 > 0 ? D / 64 : 1];
+  __shared__ float wts[64];
   const int G = Hq / Hkv;
   const int bi = blockIdx.x;  // b * Hq + i
   const int b = bi / Hq, i = bi - b * Hq;
   const int g = i / G, gg = i - g * G;
   const int u = b * Hkv + g;
-  const int d = threadIdx.x;
-  const float kn = widen1(k_new[(size_t)u * D + d]);
-  const float vn = widen1(v_new[(size_t)u * D + d]);
+  const int d = threadIdx.x, lane = d & 63;
+  // Everything that does not depend on another load is requested here, in one round trip: the launch is short and
+  // latency-bound, so the number of dependent round trips is its cost.
+  const T kn_raw = k_new[(size_t)u * D + d], vn_raw = v_new[(size_t)u * D + d];
+  const float kn = widen1(kn_raw), vn = widen1(vn_raw);
+  const float qd = widen1(q[(size_t)bi * D + d]) * qscale;
+  const int i0 = item_off[u], i1 = item_off[u + 1];
+  const bool keep_new = new_flags == nullptr || new_flags[u] != 0;
+  const int n_len = len[u];
+  const int64_t r0 = row_off[u], cap = row_off[u + 1] - r0;
+
+  // A batch of up to 64 item records: lane j takes the maximum and sum of record base + j; every thread also
+  // requests its column of the batch's first 8 records, so that they travel together with the maxima.
+  auto request = [&](int base, float &mj, float &lj, float (&x)[8]) {
+    const int n = min(64, i1 - base);
+    const size_t pr = (size_t)(base + lane) * G + gg;
+    mj = lane < n ? pm[pr] : -INFINITY;
+    lj = lane < n ? pl[pr] : 0.f;
+    const float *col = pacc + ((size_t)base * G + gg) * D + d;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = e < n ? col[(size_t)e * G * D] : 0.f;
+  };
+  float mj = -INFINITY, lj = 0.f, x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (i0 < i1) request(i0, mj, lj, x);
+
   // self score: scale * q . k_new (in log2 units)
-  float part = widen1(q[(size_t)bi * D + d]) * qscale * kn;
+  float part = qd * kn;
   for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
   if ((d & 63) == 0) red[d >> 6] = part;
   __syncthreads();
@@ -280,17 +303,11 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
 #pragma unroll
   for (int w = 0; w < (D + 63) / 64; ++w) s_self += red[w];
 
-  // item records of this (batch, head), 64 at a time: lane j takes record i0 + j, the wave reduces the maximum
-  // and the sum, the weights go through LDS, and every thread then adds its column with independent loads
-  __shared__ float wts[64];
-  const int i0 = item_off[u], i1 = item_off[u + 1];
-  const int lane = d & 63;
   float M = s_self, L = 1.f, A = vn;  // state so far: the new token alone, relative to M
   // recent-token ring (Table 5): an evicted token among the n_recent - 1 positions before `pos` is still visible
   // (the kept ones are cache rows already).  Slot contents are block-uniform, so the branches are too.
   if (ring.k) {
     const T *rk = static_cast<const T *>(ring.k), *rv = static_cast<const T *>(ring.v);
-    const float qd = widen1(q[(size_t)bi * D + d]) * qscale;
     for (int w = 0; w < ring.n; ++w) {
       const size_t slot = (size_t)u * ring.n + w;
       const int p = ring.pos[slot];
@@ -302,7 +319,7 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
       __syncthreads();
       float sr = 0.f;
 #pragma unroll
-      for (int x = 0; x < (D + 63) / 64; ++x) sr += red[x];
+      for (int xw = 0; xw < (D + 63) / 64; ++xw) sr += red[xw];
       const float M_new = fmaxf(M, sr);
       const float keep = exp2f(M - M_new), pr = exp2f(sr - M_new);
       M = M_new;
@@ -310,11 +327,11 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
       A = fmaf(pr, widen1(rv[slot * D + d]), A * keep);
     }
   }
+  // the wave reduces the batch's maximum and sum, the weights go through LDS, and every thread then adds its
+  // column with independent loads
   for (int base = i0; base < i1; base += 64) {
     const int n = min(64, i1 - base);
-    const size_t pr = (size_t)(base + lane) * G + gg;
-    const float mj = lane < n ? pm[pr] : -INFINITY;
-    const float lj = lane < n ? pl[pr] : 0.f;
+    if (base != i0) request(base, mj, lj, x);
     float mb = mj;
     for (int o = 32; o > 0; o >>= 1) mb = fmaxf(mb, __shfl_xor(mb, o, 64));
     const float M_new = fmaxf(M, mb);
@@ -329,26 +346,26 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
     L = L * keep + lsum;
     A *= keep;
     const float *col = pacc + ((size_t)base * G + gg) * D + d;
-    int j = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) A = fmaf(e < n ? wts[e] : 0.f, x[e], A);
+    int j = 8;
     for (; j + 8 <= n; j += 8) {
-      float x[8];
+      float y[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = col[(size_t)(j + e) * G * D];
+      for (int e = 0; e < 8; ++e) y[e] = col[(size_t)(j + e) * G * D];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) A = fmaf(wts[j + e], x[e], A);
+      for (int e = 0; e < 8; ++e) A = fmaf(wts[j + e], y[e], A);
     }
     for (; j < n; ++j) A = fmaf(wts[j], col[(size_t)j * G * D], A);
   }
   narrow1(A / L, &out[(size_t)bi * D + d]);
 
-  if (gg == 0 && (new_flags == nullptr || new_flags[u] != 0)) {
-    const int n = len[u];
-    const int64_t r0 = row_off[u], cap = row_off[u + 1] - r0;
+  if (gg == 0 && keep_new) {
     __syncthreads();  // every thread has read len[u] before it changes
-    if (n < cap) {
-      kc[(size_t)(r0 + n) * D + d] = k_new[(size_t)u * D + d];
-      vc[(size_t)(r0 + n) * D + d] = v_new[(size_t)u * D + d];
-      if (d == 0) { idx[r0 + n] = pos; len[u] = n + 1; }
+    if (n_len < cap) {
+      kc[(size_t)(r0 + n_len) * D + d] = kn_raw;
+      vc[(size_t)(r0 + n_len) * D + d] = vn_raw;
+      if (d == 0) { idx[r0 + n_len] = pos; len[u] = n_len + 1; }
     } else if (d == 0) {
       atomicOr(d_err, 1);
     }
@@ -358,10 +375,10 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
   // the old position (out of the window) or the new one (not before pos).
   if (ring.k && gg == 0) {
     const size_t slot = (size_t)u * ring.n + (size_t)(pos % ring.n);
-    static_cast<T *>(ring.k)[slot * D + d] = k_new[(size_t)u * D + d];
-    static_cast<T *>(ring.v)[slot * D + d] = v_new[(size_t)u * D + d];
+    static_cast<T *>(ring.k)[slot * D + d] = kn_raw;
+    static_cast<T *>(ring.v)[slot * D + d] = vn_raw;
     if (d == 0) {
-      ring.flags[slot] = (new_flags == nullptr || new_flags[u] != 0) ? 1 : 0;
+      ring.flags[slot] = keep_new ? 1 : 0;
       ring.pos[slot] = pos;
     }
   }
