@@ -18,6 +18,9 @@
  *     workspace too small, launch failure).  A cache row that would exceed a unit's capacity is never
  *     written; the kernel records it in a sticky device word that ag_poll_error reports.
  *   - No C++ exception crosses this boundary.  An ag_ctx is not thread-safe; distinct contexts are.
+ *   - The calls of one context share its workspace and a few arrival counters that are zero between launches:
+ *     work enqueued through one context must not overlap on the device (use one stream, or order the streams
+ *     with events); give work that is meant to run concurrently a context of its own.
  *   - Flags: uint8, 1 (any non-zero) = retain, 0 = evict, stored head-major [B, Hkv, L].
  *   - GQA: query head i reads KV head i / (Hq / Hkv); flags and caches are per KV head.
  *   - Supported: dtype bf16 with D = 128 or 64 (MFMA path) and fp32 with D <= 256 (plain-ALU path);
