@@ -99,8 +99,8 @@ __global__ __launch_bounds__(256) void ag_gate_mfma_kernel(const uint16_t *__res
 // A operand's 16-byte feature loads.  Columns n >= H_f read whatever follows in LDS; they only reach output
 // columns that are never stored.  Otherwise wp holds the fragments prepared by ag_gate_pack_w.
 constexpr int kFusedWaves = 8;
-template <bool RAW>
-__global__ __launch_bounds__(64 * kFusedWaves) void ag_gate_fused_kernel(
+template <bool RAW, int PF>
+__global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fused_kernel(
     const uint16_t *__restrict__ x, const uint4 *__restrict__ wp, int64_t tokens, int d_in, int L, int H_f,
     const float *__restrict__ bias, float thr, int n_sink, float *__restrict__ logits, uint8_t *__restrict__ flags,
     float *__restrict__ partial, int32_t *__restrict__ tickets) {
@@ -133,7 +133,6 @@ __global__ __launch_bounds__(64 * kFusedWaves) void ag_gate_fused_kernel(
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  constexpr int PF = 4;
   for (int c0 = c_lo + wave; c0 < c_hi; c0 += kFusedWaves * PF) {
     uint4 a[PF][4], b[PF][4];
     // W first: its loads hit the L2 and return early, so the staging below runs while the feature rows are
@@ -365,12 +364,19 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
     if (fused) {
       const dim3 grid((unsigned)tiles32, fsplits), block(64 * kFusedWaves);
       ag_tick(ctx, AG_K_GATE, s);
-      if (raw_w)
-        hipLaunchKernelGGL(ag_gate_fused_kernel<true>, grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)w,
-                           tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags, partial, tickets);
-      else
-        hipLaunchKernelGGL(ag_gate_fused_kernel<false>, grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)wp,
-                           tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags, partial, tickets);
+      // PF = feature chunks a wave keeps in flight.  A launch of at most one workgroup per CU is one round of loads
+      // per wave (PF = 4); a longer one runs two workgroups per CU with half the registers (PF = 2), so that one
+      // loads while the other reduces and writes its flags.
+      const bool two_per_cu = (int64_t)tiles32 * fsplits > ctx->num_cu;
+#define AG_GATE_FUSED(RAWV, PFV, WPTR)                                                                             \
+  hipLaunchKernelGGL((ag_gate_fused_kernel<RAWV, PFV>), grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)(WPTR), \
+                     tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags, partial, tickets)
+      if (raw_w) {
+        if (two_per_cu) AG_GATE_FUSED(true, 2, w); else AG_GATE_FUSED(true, 4, w);
+      } else {
+        AG_GATE_FUSED(false, 4, wp);  // measured: the pre-packed path is slower with two workgroups per CU
+      }
+#undef AG_GATE_FUSED
       ag_tock(ctx, AG_K_GATE, s);
       return hipGetLastError();
     }
