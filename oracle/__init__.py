@@ -107,6 +107,20 @@ def gate_mha(x, w_qkv, h_prime: int, d_prime: int, w_o, bias, tau: float, n_sink
     return gate(feat, w_o, bias, tau, n_sink)
 
 
+def project_kv(x, w_kv, Hkv: int, D: int, store=None):
+    """The layer's own key/value projection (Eq. 2: K_i = X W_i^K, V_i = X W_i^V) in the layout the path consumes.
+
+    x [B,L,d]; w_kv [d, 2*Hkv*D] with the K columns of all heads first (head h at columns h*D .. h*D+D-1), then the
+    V columns in the same order.  The product is a library matmul in fp64; `store` names the dtype in which K and V
+    are then held ("bf16" rounds to nearest even, None = exact).  Returns (k, v), each f64 [B,Hkv,L,D]."""
+    x, w_kv = np.asarray(_f32(x), dtype=np.float64), np.asarray(_f32(w_kv), dtype=np.float64)
+    B, L, d = x.shape
+    assert w_kv.shape == (d, 2 * Hkv * D)
+    proj = _round_to(x.reshape(B * L, d) @ w_kv, store).reshape(B, L, 2, Hkv, D)
+    k, v = (np.ascontiguousarray(proj[:, :, i].transpose(0, 2, 1, 3)) for i in range(2))
+    return k, v
+
+
 def prefill_attn(q, k, v, flags, scale: float, n_recent: int = 1) -> np.ndarray:
     """q [B,Hq,L,D], k/v [B,Hkv,L,D], flags u8 [B,Hkv,L] -> out f64 [B,Hq,L,D]."""
     q, k, v = _f32(q), _f32(k), _f32(v)

@@ -420,3 +420,36 @@ def test_decode_len_after_many_steps_counts_flags():
     for u in range(3):
         new_idx = cache.idx[ro[u] + lens[u]:ro[u] + cache.len[u]]
         assert (np.diff(new_idx) > 0).all()
+
+
+# ------------------------------------------------------------------ K/V projection (Eq. 2)
+def test_project_kv_selector_weights_read_out_the_features():
+    """W that copies feature block h into head h: K_h = X[:, hD:(h+1)D] and V_h = -X[:, ...] exactly, which pins the
+    column order (K heads first, then V heads), the head-major output layout and the absence of any scaling."""
+    B, L, H, D = 2, 5, 3, 4
+    d = H * D
+    x = rnd(71, B, L, d)
+    w = np.zeros((d, 2 * H * D), np.float32)
+    for c in range(H * D):
+        w[c, c] = 1.0
+        w[c, H * D + c] = -1.0
+    k, v = oracle.project_kv(x, w, H, D)
+    for h in range(H):
+        assert np.array_equal(k[:, h], x[:, :, h * D:(h + 1) * D].astype(np.float64))
+        assert np.array_equal(v[:, h], -x[:, :, h * D:(h + 1) * D].astype(np.float64))
+
+
+def test_project_kv_matches_per_element_sums_and_rounds_to_bf16_on_request():
+    B, L, d, H, D = 1, 3, 6, 2, 2
+    x, w = rnd(72, B, L, d), rnd(73, d, 2 * H * D)
+    k, v = oracle.project_kv(x, w, H, D)
+    for t in range(L):
+        for h in range(H):
+            for e in range(D):
+                want_k = sum(float(x[0, t, c]) * float(w[c, h * D + e]) for c in range(d))
+                want_v = sum(float(x[0, t, c]) * float(w[c, H * D + h * D + e]) for c in range(d))
+                assert abs(k[0, h, t, e] - want_k) < 1e-12 and abs(v[0, h, t, e] - want_v) < 1e-12
+    kb, _ = oracle.project_kv(x, w, H, D, store="bf16")
+    bits = kb.astype(np.float32).view(np.uint32)
+    assert np.all(bits & 0xffff == 0)                       # representable in bf16
+    assert np.all(np.abs(kb - k) <= np.abs(k) * 2.0 ** -8)  # and the nearest such value (half a spacing at most)
