@@ -181,6 +181,24 @@ ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, c
                                  float scale, const ag_kv_cache *cache, int n_recent, void *out);
 
 /*
+ * The layer's own key/value projection (Eq. 2: K = X W^K, V = X W^V) fused with ag_compact_kv, for bf16 and head
+ * size 128: the kept rows go from the projection's accumulators straight into the cache, so the compaction pass
+ * and its second read of K and V disappear (the kernel fusion the paper's Sec. 5 leaves as future work).
+ *   x      [B, L, d_model] bf16, d_model % 64 == 0
+ *   w_kv   [d_model, 2 * Hkv * 128] bf16: the K columns of all heads (head h at columns 128 h ..), then the V columns
+ *   flags  [B, Hkv, L]
+ *   kv_out one allocation of two [B, Hkv, L, 128] bf16 tensors back to back, k then v: every token's own k, v, which
+ *          the diagonal of Eq. 5 needs whether the token is kept or not (pass them to ag_prefill_attn as k, v)
+ *   cache  as in ag_compact_kv (B, Hkv from the cache; D = 128, bf16; row_off filled by the caller): receives the
+ *          kept rows, idx = pos0 + t and len; rows beyond a unit's capacity are dropped (ag_poll_error)
+ * The cache rows are bit-identical to the rows of kv_out they copy.  AG_EUNSUPPORTED for other dtypes or sizes.
+ */
+size_t ag_project_compact_workspace_bytes(int B, int L, int Hkv);
+ag_status ag_project_compact_kv(ag_ctx *ctx, void *hip_stream, const void *x, ag_dtype dtype, int B, int L,
+                                int d_model, const void *w_kv, const uint8_t *flags, int pos0, void *kv_out,
+                                ag_kv_cache *cache);
+
+/*
  * ag_compact_kv followed by ag_prefill_attn_recent on the same k, v, flags, as one call that scans the flags once:
  * `cache` (row_off filled by the caller) receives the compacted rows, idx (pos0 + t) and len exactly as from
  * ag_compact_kv, and out the attention over them.  The prefilling stage of one layer (Sec. 3.1, Sec. 3.3).

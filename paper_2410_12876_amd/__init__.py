@@ -25,7 +25,7 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
            "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
-           "ag_compact_prefill_attn", "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
+           "ag_compact_prefill_attn", "ag_project_compact_kv", "ag_project_compact_workspace_bytes", "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
 
 
 class ag_recent_ring(C.Structure):
@@ -92,6 +92,10 @@ def load() -> C.CDLL:
     lib.ag_compact_prefill_attn.restype = C.c_int
     lib.ag_compact_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32,
                                             C.POINTER(ag_kv_cache), i32, vp]
+    lib.ag_project_compact_workspace_bytes.restype = C.c_size_t
+    lib.ag_project_compact_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.ag_project_compact_kv.restype = C.c_int
+    lib.ag_project_compact_kv.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, C.POINTER(ag_kv_cache)]
     lib.ag_decode_attn.restype = C.c_int
     lib.ag_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache), vp]
     lib.ag_gate_mha_workspace_bytes.restype = C.c_size_t
@@ -219,6 +223,18 @@ def ag_compact_kv(ctx: Context, k, v, flags, pos0: int, cache: KVCache, stream=N
     L = k.shape[2]
     ctx._check(ctx._lib.ag_compact_kv(ctx._h, _stream_ptr(stream), _ptr(k), _ptr(v), _ptr(flags), L, pos0,
                                       C.byref(cache.c)))
+
+
+def project_compact_workspace_bytes(B: int, L: int, Hkv: int) -> int:
+    return int(load().ag_project_compact_workspace_bytes(B, L, Hkv))
+
+
+def ag_project_compact_kv(ctx: Context, x, w_kv, flags, pos0: int, kv_out, cache: KVCache, stream=None) -> None:
+    """x [B, L, d] bf16, w_kv [d, 2*Hkv*128] bf16 (K columns, then V columns), flags u8 [B, Hkv, L] ->
+    kv_out [2, B, Hkv, L, 128] (k, v of every token) and cache (kept rows, idx, len)."""
+    B, L, d = x.shape
+    ctx._check(ctx._lib.ag_project_compact_kv(ctx._h, _stream_ptr(stream), _ptr(x), _dtype_code(x), B, L, d, _ptr(w_kv),
+                                              _ptr(flags), pos0, _ptr(kv_out), C.byref(cache.c)))
 
 
 def ag_prefill_attn(ctx: Context, q, k, v, flags, scale: float, cache: Optional[KVCache], out, stream=None) -> None:

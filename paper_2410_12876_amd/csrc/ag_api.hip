@@ -296,6 +296,39 @@ ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void
   return AG_OK;
 }
 
+size_t ag_project_compact_workspace_bytes(int B, int L, int Hkv) {
+  if (B <= 0 || L <= 0 || Hkv <= 0) return 0;
+  return ag_ws_project_compact_bytes(B * Hkv, L);
+}
+
+ag_status ag_project_compact_kv(ag_ctx *ctx, void *hip_stream, const void *x, ag_dtype dtype, int B, int L,
+                                int d_model, const void *w_kv, const uint8_t *flags, int pos0, void *kv_out,
+                                ag_kv_cache *cache) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(x && w_kv && flags && kv_out && cache, AG_EINVAL, "ag_project_compact_kv: null pointer");
+  AG_REQUIRE(B > 0 && L > 0 && d_model > 0, AG_EINVAL, "ag_project_compact_kv: B, L, d_model must be positive");
+  AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_project_compact_kv: L = %d exceeds %d", L, kMaxL);
+  ag_status st = check_cache(ctx, cache);
+  if (st != AG_OK) return st;
+  AG_REQUIRE(cache->B == B, AG_EINVAL, "ag_project_compact_kv: cache->B = %d but B = %d", cache->B, B);
+  AG_REQUIRE(dtype == AG_BF16 && cache->dtype == AG_BF16 && cache->D == 128, AG_EUNSUPPORTED,
+             "ag_project_compact_kv: bf16 with head size 128 only");
+  AG_REQUIRE(d_model % 64 == 0, AG_EUNSUPPORTED, "ag_project_compact_kv: d_model %% 64 != 0 (got %d)", d_model);
+  AG_REQUIRE((int64_t)B * L * d_model * 2 < (int64_t)1 << 31 && (int64_t)d_model * 2 * cache->Hkv * 128 * 2 < (int64_t)1 << 31,
+             AG_EUNSUPPORTED, "ag_project_compact_kv: x or w_kv exceeds 2 GiB (the tile loaders use 32-bit offsets)");
+  const int units = B * cache->Hkv;
+  AG_REQUIRE(ag_ws_project_compact_bytes(units, L) <= ctx->ws_bytes, AG_EWORKSPACE,
+             "ag_project_compact_kv: workspace of %zu bytes is too small", ctx->ws_bytes);
+  st = need_device(ctx);
+  if (st != AG_OK) return st;
+  ws_cursor ws = cursor(ctx);
+  hipError_t e = ag_launch_project_compact(ctx, (hipStream_t)hip_stream, x, B, L, d_model, w_kv, cache->Hkv, flags, pos0,
+                                           kv_out, cache->k, cache->v, cache->idx, cache->row_off, cache->len, ws);
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_project_compact_kv: workspace too small (need %zu)", ws.off);
+  AG_HIP(e);
+  return AG_OK;
+}
+
 ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const void *k, const void *v,
                           const uint8_t *flags, int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, float scale,
                           const ag_kv_cache *cache, void *out) {

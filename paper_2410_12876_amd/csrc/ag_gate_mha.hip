@@ -45,9 +45,25 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 //   x [M, K] bf16 row-major, w [K, N] bf16 row-major, K % 64 == 0, N % 128 == 0, N = 3 * hp * 128.
 //   out: three tensors [B, hp, L, 128] back to back; token m = b * L + t.
 // grid = (N / 128, ceil(M / 128)); 4 waves, wave (wn, wm) owns the 64 x 64 quadrant of the tile.
+//
+// COMPACT (the layer's own K/V projection, N = 2 * hp * 128: K columns, then V columns): besides the two full tensors
+// -- every token needs its own k, v for the diagonal of Eq. 5 -- a tile, which is 128 tokens of one head, also
+// writes the rows of its kept tokens straight into the ragged cache, at the position the flag scan gives them
+// (words / blk_off: 64-bit keep masks and their exclusive prefix counts), so the compaction pass and its re-read of
+// K and V disappear.  The K tiles also write idx, the first token tile of a K head writes len.
+struct ag_proj_compact {
+  const uint64_t *words;    // [units, nw]
+  const int32_t *blk_off;   // [units, nw + 1]
+  const int64_t *row_off;   // [units + 1]
+  uint16_t *kc, *vc;        // cache rows
+  int32_t *idx, *len, *d_err;
+  int nw, pos0;
+};
+
+template <bool COMPACT>
 __global__ __launch_bounds__(256, 2) void ag_proj_gemm_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w,
                                                               int64_t M, int K, int N, int L, int hp,
-                                                              uint16_t *__restrict__ out) {
+                                                              uint16_t *__restrict__ out, ag_proj_compact cp) {
   __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * kXTileB + 2 * kWTileB];  // [X0][X1][W0][W1]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -155,11 +171,27 @@ __global__ __launch_bounds__(256, 2) void ag_proj_gemm_kernel(const uint16_t *__
 
   // ---- epilogue: acc[nt][mt][r] = C[token m0 + 64 wm + 32 mt + col][n0 + 64 wn + 32 nt + 8 (r/4) + 4 kb + r%4] ----
   const int hd = hp * kDh;
+  const int which_t = n0 / hd, head_t = (n0 - which_t * hd) / kDh;  // the tile is one head of one projection
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
     const int64_t m = m0 + 64 * wm + 32 * mt + col;
     if (m >= M) continue;
     const int64_t b = m / L, tt = m - b * L;
+    uint16_t *crow = nullptr;  // COMPACT: this token's row in the cache, if it is kept and fits
+    if (COMPACT) {
+      const int u = (int)b * hp + head_t;
+      const uint64_t word = cp.words[(size_t)u * cp.nw + (tt >> 6)];
+      if ((word >> (tt & 63)) & 1ull) {
+        const int c = cp.blk_off[(size_t)u * (cp.nw + 1) + (tt >> 6)] + __popcll(word & ((1ull << (tt & 63)) - 1ull));
+        const int64_t r0 = cp.row_off[u], cap = cp.row_off[u + 1] - r0;
+        if (c < cap) {
+          crow = (which_t == 0 ? cp.kc : cp.vc) + (size_t)(r0 + c) * kDh;
+          if (which_t == 0 && wn == 0 && kb == 0) cp.idx[r0 + c] = cp.pos0 + (int)tt;
+        } else if (which_t == 0 && wn == 0 && kb == 0) {
+          atomicOr(cp.d_err, 1);  // the row is dropped, nothing is written out of bounds
+        }
+      }
+    }
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -169,9 +201,19 @@ __global__ __launch_bounds__(256, 2) void ag_proj_gemm_kernel(const uint16_t *__
         const int head = rem / kDh, dd = rem - head * kDh;
         uint16_t *dst = out + (((size_t)which * (M / L) * hp + (size_t)b * hp + head) * L + tt) * kDh + dd;
         const f32x16 &c = acc[nt][mt];
-        *reinterpret_cast<uint2 *>(dst) =
-            make_uint2(pack2(c[4 * r4 + 0], c[4 * r4 + 1]), pack2(c[4 * r4 + 2], c[4 * r4 + 3]));
+        const uint2 val = make_uint2(pack2(c[4 * r4 + 0], c[4 * r4 + 1]), pack2(c[4 * r4 + 2], c[4 * r4 + 3]));
+        *reinterpret_cast<uint2 *>(dst) = val;
+        if (COMPACT && crow) *reinterpret_cast<uint2 *>(crow + dd) = val;
       }
+  }
+  if (COMPACT && which_t == 0) {  // the K tile that holds a sequence's first token writes the unit's length
+    const int64_t bb = (m0 + L - 1) / L + tid;  // thread t: the t-th sequence that starts inside this tile
+    if (bb * L < m0 + kBM && bb * L < M) {
+      const int u = (int)bb * hp + head_t;
+      const int64_t cap = cp.row_off[u + 1] - cp.row_off[u];
+      const int kept = cp.blk_off[(size_t)u * (cp.nw + 1) + cp.nw];
+      cp.len[u] = (int)(kept < cap ? kept : cap);
+    }
   }
 }
 
@@ -215,8 +257,8 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
   if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
 
   ag_tick(ctx, AG_K_MHA_PROJ, s);
-  hipLaunchKernelGGL(ag_proj_gemm_kernel, dim3(N / kBNc, (unsigned)((tokens + kBM - 1) / kBM)), dim3(256), 0, s,
-                     (const uint16_t *)x, (const uint16_t *)w_qkv, tokens, d_model, N, L, hp, qkv);
+  hipLaunchKernelGGL(ag_proj_gemm_kernel<false>, dim3(N / kBNc, (unsigned)((tokens + kBM - 1) / kBM)), dim3(256), 0, s,
+                     (const uint16_t *)x, (const uint16_t *)w_qkv, tokens, d_model, N, L, hp, qkv, ag_proj_compact{});
   ag_tock(ctx, AG_K_MHA_PROJ, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -231,4 +273,29 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
   ag_tock(ctx, AG_K_MHA_ATTN, s);
   if (e != hipSuccess) return e;
   return ag_launch_gate(ctx, s, feat, AG_BF16, B, L, hp * kDh, w_o, bias, H_f, thr, n_sink, logits, flags, ws);
+}
+
+// K/V projection with the compaction in its epilogue.  k_out and v_out must be one allocation of two
+// [B, Hkv, L, 128] tensors back to back (k first).
+size_t ag_ws_project_compact_bytes(int units, int L) {
+  return ag_ws_scan_bytes(units, L) + 4096;
+}
+
+hipError_t ag_launch_project_compact(ag_ctx *ctx, hipStream_t s, const void *x, int B, int L, int d_model,
+                                     const void *w_kv, int Hkv, const uint8_t *flags, int pos0, void *kv_out,
+                                     void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
+                                     ws_cursor &ws) {
+  const int64_t tokens = (int64_t)B * L;
+  const int units = B * Hkv, nw = ag_nwords(L), N = 2 * Hkv * kDh;
+  uint64_t *words = ws.take<uint64_t>((size_t)units * nw);
+  int32_t *blk_off = ws.take<int32_t>((size_t)units * (nw + 1));
+  if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
+  hipError_t e = ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off, nullptr);
+  if (e != hipSuccess) return e;
+  const ag_proj_compact cp{words, blk_off, row_off, (uint16_t *)kc, (uint16_t *)vc, idx, len, ctx->d_err, nw, pos0};
+  ag_tick(ctx, AG_K_MHA_PROJ, s);
+  hipLaunchKernelGGL(ag_proj_gemm_kernel<true>, dim3(N / kBNc, (unsigned)((tokens + kBM - 1) / kBM)), dim3(256), 0, s,
+                     (const uint16_t *)x, (const uint16_t *)w_kv, tokens, d_model, N, L, Hkv, (uint16_t *)kv_out, cp);
+  ag_tock(ctx, AG_K_MHA_PROJ, s);
+  return hipGetLastError();
 }

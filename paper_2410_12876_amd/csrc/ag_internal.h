@@ -114,6 +114,14 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
                               int hp, const void *w_o, const float *bias, int H_f, float thr, int n_sink, float scale,
                               float *logits, uint8_t *flags, ws_cursor &ws);
 
+// The layer's K/V projection (bf16, head size 128) with the compaction in the GEMM's epilogue.  kv_out = two
+// [B, Hkv, L, 128] tensors back to back (k, then v).
+size_t ag_ws_project_compact_bytes(int units, int L);
+hipError_t ag_launch_project_compact(ag_ctx *ctx, hipStream_t s, const void *x, int B, int L, int d_model,
+                                     const void *w_kv, int Hkv, const uint8_t *flags, int pos0, void *kv_out,
+                                     void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
+                                     ws_cursor &ws);
+
 // Device view of an ag_recent_ring (k == nullptr: no ring).  Slot w of unit u is element u * n + w.
 struct ag_ring_dev {
   void *k, *v;      // [units, n, D]

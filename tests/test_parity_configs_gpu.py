@@ -561,3 +561,81 @@ def test_decode_shape_sweep(seed):
     len0[g.integers(0, B * Hkv)] = 0
     wl = W.decode_batch(40 + seed, "t", dtype, B, Hkv * G, Hkv, D, len0, 5, pos0=max_len + 1)
     check_decode(wl, 5, 0.5, dtype)
+
+
+# ------------------------------------------------------------------ K/V projection fused with the compaction
+@pytest.mark.parametrize("B,L,d,Hkv,keep,cap_extra", [(1, 300, 256, 2, 0.5, 4), (3, 100, 128, 4, 0.3, 0), (2, 257, 512, 1, 0.9, 2),
+                                                      (1, 4096, 4096, 32, None, 8), (2, 640, 1024, 8, 0.0, 1),
+                                                      (1, 200, 64, 3, 1.0, -50)])
+def test_project_compact_kv(B, L, d, Hkv, keep, cap_extra):
+    """ag_project_compact_kv against the oracle's projection (Eq. 2) followed by its compaction.  The full K, V agree
+    with the fp64 product rounded to bf16 up to one bf16 spacing (the kernel accumulates in fp32); idx and len are
+    bit-exact; every cache row is bit-identical to the row of the kernel's own K, V that it copies.  The last case
+    gives the units less room than they keep: the surplus rows are dropped and reported."""
+    D = 128
+    g = np.random.default_rng(300 + L)
+    x = W.store((0.5 * g.standard_normal((B, L, d))).astype(np.float32), "bf16")
+    w = W.store((g.standard_normal((d, 2 * Hkv * D)) / math.sqrt(d)).astype(np.float32), "bf16")
+    if keep is None:
+        rho = 0.2 + 0.7 * g.random((1, Hkv, 1))
+        flags = (g.random((B, Hkv, L)) < rho).astype(np.uint8)
+    else:
+        flags = (g.random((B, Hkv, L)) < keep).astype(np.uint8)
+    U = B * Hkv
+    cap = max(1, int(flags.reshape(U, L).sum(1).max()) + cap_extra)
+    ro = oracle.slab_row_off(U, cap)
+    cache = new_cache(B, Hkv, D, torch.bfloat16, ro)
+    cache.idx.fill_(-7)
+    kv = torch.zeros(2, B, Hkv, L, D, dtype=torch.bfloat16, device=DEV)
+    ws = max(ag.project_compact_workspace_bytes(B, L, Hkv), 1 << 20)
+    ctx = ag.Context(0, ws)
+    ag.ag_project_compact_kv(ctx, dev(x), dev(w), dev(flags), 11, kv, cache)
+    torch.cuda.synchronize()
+    want_k, want_v = oracle.project_kv(x.f32, w.f32, Hkv, D, store="bf16")
+    got_k, got_v = host_f32(kv[0]).astype(np.float64), host_f32(kv[1]).astype(np.float64)
+    for got, want in ((got_k, want_k), (got_v, want_v)):
+        # one bf16 spacing of the larger magnitude, plus the fp32 accumulation error of a d-term sum near zero
+        tol = np.maximum(np.abs(want), np.abs(got)) * 2.0 ** -7 + 1e-5 * math.sqrt(d)
+        assert np.all(np.abs(got - want) <= tol)
+        assert np.mean(got != want) < 0.05   # the two roundings rarely disagree
+    ref, over = oracle.compact_kv(host_bits(kv[0]), host_bits(kv[1]), flags, ro, pos0=11)
+    if cap_extra >= 0:
+        assert over == 0
+        ctx.poll_error()
+    else:
+        assert over > 0
+        with pytest.raises(ag.AgError):
+            ctx.poll_error()
+    assert np.array_equal(cache.len.cpu().numpy(), ref.len)
+    gk, gv, gi = host_bits(cache.k), host_bits(cache.v), cache.idx.cpu().numpy()
+    for u in range(U):
+        a, n = int(ro[u]), int(ref.len[u])
+        assert np.array_equal(gk[a:a + n], ref.k[a:a + n]) and np.array_equal(gv[a:a + n], ref.v[a:a + n])
+        assert np.array_equal(gi[a:a + n], ref.idx[a:a + n])
+        assert (gi[a + n:int(ro[u + 1])] == -7).all()   # nothing written behind the valid rows
+    ctx.close()
+
+
+def test_project_compact_kv_feeds_the_prefill():
+    """The fused call's outputs are what ag_prefill_attn expects: same result as project -> ag_compact_kv."""
+    B, L, d, H, D = 1, 512, 512, 4, 128
+    g = np.random.default_rng(333)
+    x = W.store((0.5 * g.standard_normal((B, L, d))).astype(np.float32), "bf16")
+    w = W.store((g.standard_normal((d, 2 * H * D)) / math.sqrt(d)).astype(np.float32), "bf16")
+    q = W.store(g.standard_normal((B, H, L, D)).astype(np.float32), "bf16")
+    flags = (g.random((B, H, L)) < 0.5).astype(np.uint8)
+    ro = oracle.slab_row_off(B * H, L)
+    ctx = make_ctx(B, L, H, H, D, ag.AG_BF16)
+    kv = torch.zeros(2, B, H, L, D, dtype=torch.bfloat16, device=DEV)
+    c1 = new_cache(B, H, D, torch.bfloat16, ro)
+    ag.ag_project_compact_kv(ctx, dev(x), dev(w), dev(flags), 0, kv, c1)
+    c2 = new_cache(B, H, D, torch.bfloat16, ro)
+    ag.ag_compact_kv(ctx, kv[0], kv[1], dev(flags), 0, c2)
+    o1, o2 = (torch.empty(B, H, L, D, dtype=torch.bfloat16, device=DEV) for _ in range(2))
+    ag.ag_prefill_attn(ctx, dev(q), kv[0], kv[1], dev(flags), 1 / math.sqrt(D), c1, o1)
+    ag.ag_prefill_attn(ctx, dev(q), kv[0], kv[1], dev(flags), 1 / math.sqrt(D), c2, o2)
+    torch.cuda.synchronize()
+    assert torch.equal(c1.len, c2.len) and torch.equal(o1, o2)
+    ref = oracle.prefill_attn(q.f32, host_f32(kv[0]), host_f32(kv[1]), flags, 1 / math.sqrt(D))
+    assert attn_error("bf16", host_f32(o1), ref) <= attn_tolerance("bf16", ref)
+    ctx.close()
