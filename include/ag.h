@@ -128,7 +128,7 @@ ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtyp
                   uint8_t *flags_out);
 
 /*
- * The paper's main gate (Sec. 3.2, Eq. 3): a small multi-head attention MHA' over the hidden states, then the
+ * The paper's main gate (Sec. 3.3, Eq. 3): a small multi-head attention MHA' over the hidden states, then the
  * gate's output projection and the threshold of Eq. 4.
  *   Q', K', V' = x w_qkv     x [B, L, d_model]; w_qkv [d_model, 3 * h_prime * d_prime], columns ordered
  *                            (Q' | K' | V'), inside each block head-major (head 0's d_prime columns first)
@@ -183,7 +183,7 @@ ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, c
 /*
  * The layer's own key/value projection (Eq. 2: K = X W^K, V = X W^V) fused with ag_compact_kv, for bf16 and head
  * size 128: the kept rows go from the projection's accumulators straight into the cache, so the compaction pass
- * and its second read of K and V disappear (the kernel fusion the paper's Sec. 5 leaves as future work).
+ * and its second read of K and V disappear (the kernel fusion that Sec. 4.2.3, "Inference Efficiency", leaves as future work).
  *   x      [B, L, d_model] bf16, d_model % 64 == 0
  *   w_kv   [d_model, 2 * Hkv * 128] bf16: the K columns of all heads (head h at columns 128 h ..), then the V columns
  *   flags  [B, Hkv, L]

@@ -85,7 +85,7 @@ def _round_to(x: np.ndarray, store) -> np.ndarray:
 
 
 def gate_mha(x, w_qkv, h_prime: int, d_prime: int, w_o, bias, tau: float, n_sink: int = 0, store=None):
-    """The main Attention-Gate module (Sec. 3.2, Eq. 3): MHA' over the hidden states, then the gate projection.
+    """The main Attention-Gate module (Sec. 3.3, Eq. 3): MHA' over the hidden states, then the gate projection.
 
     x [B,L,d]; w_qkv [d, 3*h'*d'] with column blocks (Q'|K'|V'), heads side by side inside a block;
     w_o [h'*d', H_f]; bias [H_f].  Steps, in the paper's order:

@@ -1,4 +1,4 @@
-// The paper's main Attention-Gate module (Sec. 3.2, Eq. 3): a small multi-head attention MHA' in front of the
+// The paper's main Attention-Gate module (Sec. 3.3, Eq. 3): a small multi-head attention MHA' in front of the
 // gate's output projection,
 //     Q', K', V' = X W'        (d -> h' heads of d'_k each)
 //     A          = causal softmax attention per head over the whole prompt (no eviction inside the gate)
