@@ -169,7 +169,7 @@ ag_status ag_prefill_attn(ag_ctx *ctx, void *hip_stream, const void *q, const vo
                           float scale, const ag_kv_cache *cache, void *out);
 
 /*
- * The same attention with a window of recent tokens that stay visible whatever their flag (Table 5, the
+ * The same attention with a window of recent tokens that stay visible whatever their flag (Table 6 of the appendix, the
  * "keep recent tokens" settings): the visible keys of row j are
  *   { t < j : flags[b,g,t] != 0 }  plus  { t : j - n_recent < t <= j }.
  * n_recent = 1 is ag_prefill_attn (only the diagonal); 1 <= n_recent <= 64, else AG_EINVAL.  Arguments, layouts
@@ -183,7 +183,8 @@ ag_status ag_prefill_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, c
 /*
  * The layer's own key/value projection (Eq. 2: K = X W^K, V = X W^V) fused with ag_compact_kv, for bf16 and head
  * size 128: the kept rows go from the projection's accumulators straight into the cache, so the compaction pass
- * and its second read of K and V disappear (the kernel fusion that Sec. 4.2.3, "Inference Efficiency", leaves as future work).
+ * and its second read of K and V disappear (the kernel fusion that Sec. 4.2.3, "Inference Efficiency", leaves
+ * as future work).
  *   x      [B, L, d_model] bf16, d_model % 64 == 0
  *   w_kv   [d_model, 2 * Hkv * 128] bf16: the K columns of all heads (head h at columns 128 h ..), then the V columns
  *   flags  [B, Hkv, L]
@@ -219,7 +220,7 @@ ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const voi
                          const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache, void *out);
 
 /*
- * Decoding with the recent-token window (Table 5, "keep recent tokens"): the tokens at the n_recent - 1 positions
+ * Decoding with the recent-token window (Table 6 of the appendix, "keep recent tokens"): the tokens at the n_recent - 1 positions
  * before the new one stay visible whatever their flag.  The evicted ones are not in the cache, so the last
  * n_recent tokens of every unit live in a small ring, slot = position % n_recent (caller-owned device memory):
  *   k, v   [B*Hkv, n_recent, D] in the cache's dtype;  flags uint8 [B*Hkv, n_recent] (keep flag of the token in

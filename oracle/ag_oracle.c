@@ -76,7 +76,7 @@ void ag_oracle_gate(const float *feat, const float *w, const float *bias, int B,
 
 /* Eq. 5: is key column t visible to query row j under keep-flags f (of this head)?
  * n_recent = 1 is the paper's main setting (only the diagonal is always kept); a larger
- * value also keeps the n_recent-1 keys just before the query (Table 5, settings 6-1/6-2). */
+ * value also keeps the n_recent-1 keys just before the query (Table 6 in the appendix "More Ablation", settings 6-1/6-2). */
 static inline int visible(const uint8_t *f, int j, int t, int n_recent) {
   if (t > j) return 0;            /* j < t : causal               */
   if (j - t < n_recent) return 1; /* j = t (and the recent band)  */

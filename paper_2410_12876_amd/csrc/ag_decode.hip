@@ -304,7 +304,7 @@ __global__ __launch_bounds__(D) void ag_decode_merge_kernel(const T *__restrict_
   for (int w = 0; w < (D + 63) / 64; ++w) s_self += red[w];
 
   float M = s_self, L = 1.f, A = vn;  // state so far: the new token alone, relative to M
-  // recent-token ring (Table 5): an evicted token among the n_recent - 1 positions before `pos` is still visible
+  // recent-token ring (Table 6 of the appendix): an evicted token among the n_recent - 1 positions before `pos` is still visible
   // (the kept ones are cache rows already).  Slot contents are block-uniform, so the branches are too.
   if (ring.k) {
     const T *rk = static_cast<const T *>(ring.k), *rv = static_cast<const T *>(ring.v);

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
   // One 64-key tile: rows [r0, r0 + 64) of src_k / src_v (rows outside [0, r_end) read as zero).  Compacted tiles
   // (band == false) hide keys at or past the query's boundary cnt_q.  Band tiles (band == true) come from the
   // uncompacted K/V and show only the evicted tokens (keep bit clear in bword) among the n_recent - 1 tokens just
-  // before the query: the kept ones are already among the compacted rows (Table 5, recent-token settings).
+  // before the query: the kept ones are already among the compacted rows (Table 6 of the appendix, recent-token settings).
   auto tile = [&](const uint16_t *src_k, const uint16_t *src_v, int r0, int r_end, bool band, uint64_t bword) {
     __syncthreads();  // previous tile fully consumed
     // ---- stage K tile (row-major) and V tile (transposed) in LDS ----
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(256) void ag_prefill_f32_kernel(const float *__rest
 #pragma unroll
   for (int e = 0; e < DPL; ++e) o[e] = lane + 64 * e < D ? vself[lane + 64 * e] : 0.f;
 
-  // recent-token band (Table 5): evicted tokens among the n_recent - 1 just before the query stay visible; the
+  // recent-token band (Table 6 of the appendix): evicted tokens among the n_recent - 1 just before the query stay visible; the
   // kept ones are among the cache rows already.  Wave-uniform loop, one key at a time.
   for (int i = 1; i < n_recent && j - i >= 0; ++i) {
     const int t = j - i;

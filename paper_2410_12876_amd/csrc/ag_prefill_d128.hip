@@ -77,7 +77,7 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 // GB = query heads of one KV group per workgroup (one per wave).  n_split = chunks per item in the grid,
 // chunk_tiles_dev = key tiles per chunk (device value, NULL without a split); part = partial states
 // [item][chunk][4 waves][66][64] fp32 and tickets = per-item arrival counters (n_split > 1).
-// BAND = the recent-token variant (Table 5): the evicted tokens among the n_recent - 1 tokens just before a query
+// BAND = the recent-token variant (Table 6 of the appendix): the evicted tokens among the n_recent - 1 tokens just before a query
 // stay visible to it.  They are read from the uncompacted K/V as up to three extra 64-key "band" tiles that run
 // through the same pipeline ahead of the compacted tiles of chunk 0, with their own mask.
 // NW = waves per workgroup: 4 (two workgroups per CU).  (8, one workgroup per CU with twice the queries sharing

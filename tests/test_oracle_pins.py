@@ -106,7 +106,7 @@ def test_random_flags_vs_dense_mask_with_gqa(Hq, Hkv):
 
 @pytest.mark.parametrize("n_recent", [1, 5, 10])
 def test_recent_window_vs_dense_mask(n_recent):
-    """Table 5 (6-1)/(6-2): the last n_recent keys stay visible whatever their flag."""
+    """Table 6 (appendix "More Ablation"), settings (6-1)/(6-2): the last n_recent keys stay visible whatever their flag."""
     L, D = 40, 8
     q, k, v = rnd(10, 1, 1, L, D), rnd(11, 1, 1, L, D), rnd(12, 1, 1, L, D)
     flags = (np.random.default_rng(13).random((1, 1, L)) < 0.3).astype(np.uint8)

@@ -297,7 +297,7 @@ def _prefill_recent(q, k, v, flags, scale, n_recent, with_cache=True):
     ("bf16", 1, 2, 2, 130, 128, 0.0, 5, True),       # nothing kept: plain sliding-window attention
 ])
 def test_prefill_recent_window(dtype, B, Hq, Hkv, L, D, keep, n_recent, with_cache):
-    """Table 5's recent-token settings: keys within n_recent - 1 positions before the query stay visible."""
+    """Table 6's recent-token settings (appendix "More Ablation", (6-1) and (6-2)): keys within n_recent - 1 positions before the query stay visible."""
     g = np.random.default_rng(100 + L + n_recent)
     q, k, v = (W.store(g.standard_normal(s).astype(np.float32), dtype)
                for s in ((B, Hq, L, D), (B, Hkv, L, D), (B, Hkv, L, D)))
