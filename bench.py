@@ -294,6 +294,43 @@ def decode_stack_leg(args, torch, ag, W):
             "bytes_per_token": byts, **{k + "_" + kk: vv for k, v in res.items() for kk, vv in v.items()}}
 
 
+def projection_leg(args, torch, ag, W, wl):
+    """The layer's K/V projection with the compaction in its epilogue (ag_project_compact_kv) on the headline shape,
+    beside the separate compaction it replaces.  Weights are seeded N(0, 1/d) drawn on the device."""
+    B, L, d, H, D = wl.B, wl.L, wl.d_model, wl.Hkv, wl.D
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2)
+    x = to_dev(wl.x, torch)
+    w = (torch.randn(d, 2 * H * D, device="cuda", generator=gen) / math.sqrt(d)).to(torch.bfloat16)
+    flags = torch.empty(B, H, L, dtype=torch.uint8, device="cuda")
+    U = B * H
+    ro = torch.arange(U + 1, dtype=torch.int64, device="cuda") * L
+    cache = ag.KVCache(torch.zeros(U * L, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(U * L, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(U * L, dtype=torch.int32, device="cuda"), ro,
+                       torch.zeros(U, dtype=torch.int32, device="cuda"), B, H, D)
+    kv = torch.zeros(2, B, H, L, D, dtype=torch.bfloat16, device="cuda")
+    ctx = ag.Context(0, ag.workspace_bytes(B, L, H, H, D, ag.AG_BF16, d, 0))
+    ag.ag_gate(ctx, x, to_dev(wl.w_gate, torch), torch.from_numpy(wl.bias).cuda(), wl.tau, wl.n_sink, None, flags)
+    for _ in range(3):
+        ag.ag_project_compact_kv(ctx, x, w, flags, 0, kv, cache)
+    torch.cuda.synchronize()
+    ctx.timing_enable(True)
+    for _ in range(10):
+        ag.ag_project_compact_kv(ctx, x, w, flags, 0, kv, cache)
+    for _ in range(10):
+        ag.ag_compact_kv(ctx, kv[0], kv[1], flags, 0, cache)
+    torch.cuda.synchronize()
+    t = ctx.timing_read()
+    ctx.timing_enable(False)
+    ctx.poll_error()
+    ctx.close()
+    proj_ms = t["mha_proj"][0] / t["mha_proj"][1]
+    flops = 2.0 * B * L * d * 2 * H * D
+    return {"workload": wl.name + " K/V projection, d -> 2 x %d x %d" % (H, D), "fused_projection_compaction_ms": proj_ms,
+            "tflops": flops / (proj_ms * 1e-3) / 1e12, "separate_compaction_ms": t["compact"][0] / t["compact"][1]}
+
+
 def overlap_leg(args, torch, ag, W, wl):
     """Several layers back to back: the gate of layer l+1 takes its input from before layer l's attention
     (previous-layer gating, Table 3), so it can run on a second stream (own context and workspace) beside layer
@@ -422,6 +459,8 @@ def main():
                     help="one keep ratio for every head instead of config 2's per-head U[0.2, 0.9]")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-batch", type=int, default=32)
+    ap.add_argument("--project", action="store_true",
+                    help="also time the K/V projection with the compaction in its epilogue (ag_project_compact_kv)")
     ap.add_argument("--decode-stack", action="store_true",
                     help="also time config 5's decode phase (one token through 32 layers, eager and from a HIP graph)")
     ap.add_argument("--stack-steps", type=int, default=32)
@@ -461,6 +500,7 @@ def main():
         log("[bench] timing the CPU oracle on one step ...")
         cpu = cpu_baseline(wl, W)
     overlap = None if args.skip_overlap else overlap_leg(args, torch, ag, W, wl)
+    proj = projection_leg(args, torch, ag, W, wl) if args.project and wl.x is not None else None
     stack = None
     if args.decode_stack:
         log("[bench] config 5 decode phase, 32 layers ...")
@@ -478,7 +518,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": pre["config"], "kernel_ms": pre["kernel_ms"], "roofline": pre["roofline"],
         "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
-        "next_layer_gate_overlap": overlap, "decode_stack": stack, "machine": machine,
+        "next_layer_gate_overlap": overlap, "decode_stack": stack, "kv_projection": proj, "machine": machine,
     }
     print(json.dumps(line))
 
