@@ -1,6 +1,7 @@
 // Flag-masked causal prefill attention (Eq. 2 under the mask of Eq. 5), bf16, head dimension 128 -- the
-// tuned CDNA4 kernel.  Same formulation as ag_prefill.hip (attention over the compacted rows with the
-// per-query boundary cnt[j]; the query's own key/value initialises the online softmax), built for gfx950:
+// tuned CDNA4 kernel.  Same formulation as ag_prefill.hip (attention over the compacted rows with a per-query
+// boundary: cnt[j] + 1 rows for a kept token, whose own row is cache row cnt[j]; cnt[j] rows plus its own
+// key/value from the uncompacted tensors, which initialise the online softmax, for an evicted one), built for gfx950:
 //
 //   * K and V tiles (64 cache rows x 256 B) go from global memory straight into LDS (buffer_load ... lds,
 //     no register staging), double-buffered, one workgroup barrier per step.
@@ -149,10 +150,16 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   const int64_t ro0 = row_off[u], ro1 = row_off[u + 1];
   auto cnt_in = [](uint64_t w, int pre, int j) { return pre + __popcll(w & ((1ull << (j & 63)) - 1ull)); };
   const int len_u = (int)min((int64_t)kept_u, ro1 - ro0);
-  const int cnt_q = cnt_in(word_w, pre_w, jq);
-  const int cnt_wave_lo = cnt_in(word_w, pre_w, min(j0, L - 1));
-  const int cnt_wave_hi = j0 < L ? cnt_in(word_w, pre_w, min(j0 + 31, L - 1)) : 0;
-  const int cnt_blk = min(cnt_in(word_b, pre_b, jb), len_u);
+  // A kept token's own key and value are row cnt(j) of the compacted rows, so its visible set is simply the first
+  // cnt(j) + 1 of them; only an evicted token (or one whose row did not fit the cache) takes its own k, v from the
+  // uncompacted tensors.  bnd = number of compacted rows query j sees.
+  auto in_cache = [&](uint64_t w, int pre, int j) { return ((w >> (j & 63)) & 1ull) != 0 && cnt_in(w, pre, j) < len_u; };
+  auto bnd_in = [&](uint64_t w, int pre, int j) { return cnt_in(w, pre, j) + (in_cache(w, pre, j) ? 1 : 0); };
+  const int cnt_q = bnd_in(word_w, pre_w, jq);
+  const bool own_kv = chunk == 0 && !in_cache(word_w, pre_w, jq);  // this query's diagonal term comes from k, v
+  const int cnt_wave_lo = bnd_in(word_w, pre_w, min(j0, L - 1));
+  const int cnt_wave_hi = j0 < L ? bnd_in(word_w, pre_w, min(j0 + 31, L - 1)) : 0;
+  const int cnt_blk = min(bnd_in(word_b, pre_b, jb), len_u);
   const int n_tiles = (cnt_blk + kBN - 1) / kBN;       // key tiles of the item
   const int tile0 = chunk > 0 ? chunk * chunk_tiles : 0;  // this workgroup's chunk: tiles [tile0, tile0 + n_steps)
   if (chunk > 0 && tile0 >= n_tiles) {                 // empty chunk (the whole workgroup leaves)
@@ -249,10 +256,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
 #pragma unroll
       for (int j = 0; j < LP; ++j) {
         const int row = min(j0 + RP * h + 4 * j + srow, L - 1);
-        // (all three unconditionally: the few workgroups that hold a later chunk of a split item do not use k, v)
+        // All three loads are unconditional (conditional ones end up in scratch memory).  A row whose k, v are not
+        // needed -- a kept token, or any row in a later chunk of a split item -- is pointed at the wave's first row
+        // instead, which costs one cache line per wave instead of HBM traffic per row.
+        const int kv_row = (chunk == 0 && !in_cache(word_w, pre_w, row)) ? row : min(j0, L - 1);
         sq[h][j] = *reinterpret_cast<const u32x4 *>(q + ((size_t)(b * Hq + head) * L + row) * D + 8 * schunk);
-        sk[h][j] = *reinterpret_cast<const u32x4 *>(k + ((size_t)u * L + row) * D + 8 * schunk);
-        sv[h][j] = *reinterpret_cast<const u32x4 *>(v + ((size_t)u * L + row) * D + 8 * schunk);
+        sk[h][j] = *reinterpret_cast<const u32x4 *>(k + ((size_t)u * L + kv_row) * D + 8 * schunk);
+        sv[h][j] = *reinterpret_cast<const u32x4 *>(v + ((size_t)u * L + kv_row) * D + 8 * schunk);
       }
     AG_LDS uint8_t *stage = (AG_LDS uint8_t *)smem + 3 * kTileB + w4 * (kTileB / NW);
     const int rr = col % RP;  // this lane's row inside a pass
@@ -330,16 +340,17 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       }
     }
     s_self += __shfl_xor(s_self, 32, 64);
-    m_run = s_self * qscale;
-    l_run = hb == 0 ? 1.f : 0.f;
+    // (selects, not arithmetic: what was loaded for a query that does not use it may be anything)
+    m_run = own_kv ? s_self * qscale : kEmptyMax;
+    l_run = own_kv && hb == 0 ? 1.f : 0.f;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        acc_o[dt][4 * r4 + 0] = __uint_as_float(vself[dt][r4].x << 16);
-        acc_o[dt][4 * r4 + 1] = __uint_as_float(vself[dt][r4].x & 0xffff0000u);
-        acc_o[dt][4 * r4 + 2] = __uint_as_float(vself[dt][r4].y << 16);
-        acc_o[dt][4 * r4 + 3] = __uint_as_float(vself[dt][r4].y & 0xffff0000u);
+        acc_o[dt][4 * r4 + 0] = own_kv ? __uint_as_float(vself[dt][r4].x << 16) : 0.f;
+        acc_o[dt][4 * r4 + 1] = own_kv ? __uint_as_float(vself[dt][r4].x & 0xffff0000u) : 0.f;
+        acc_o[dt][4 * r4 + 2] = own_kv ? __uint_as_float(vself[dt][r4].y << 16) : 0.f;
+        acc_o[dt][4 * r4 + 3] = own_kv ? __uint_as_float(vself[dt][r4].y & 0xffff0000u) : 0.f;
       }
   }
 
