@@ -14,6 +14,9 @@ The step is timed over --steps launches without instrumentation (eager by defaul
 graph).  Kernel durations for the roofline come from HIP event pairs that the library records around every
 kernel on the launch stream (ag_timing_* of the C ABI) over the same number of steps right after.
   machine       : what this machine sustains (MFMA loop, streaming copy, vendor bf16 GEMM) beside the data-sheet peaks.
+Optional legs: --config 4 / --config 5 --layer l (the other layer workloads), --keep, --seq-len, --decode-stack
+(config 5's decode phase: one token through 32 layers, eager and from a HIP graph), --project (the K/V projection
+with the compaction in its epilogue), next_layer_gate_overlap (the next layer's gate on a second stream).
 """
 import argparse
 import json
