@@ -116,3 +116,12 @@ def test_gate_presets_match_the_header():
     val = {m.group(1): float(m.group(2)) for m in re.finditer(r"#define (AG_(?:TAU|GAMMA)_[A-Z]+) ([0-9.]+)f", text)}
     assert (val["AG_TAU_PRETRAIN"], val["AG_GAMMA_PRETRAIN"]) == ag.PRESET_PRETRAIN == (0.5, 2.0)
     assert (val["AG_TAU_FINETUNE"], val["AG_GAMMA_FINETUNE"]) == ag.PRESET_FINETUNE == (0.3, 0.0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; --gpus N > 1 exits with a message instead of running."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
