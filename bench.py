@@ -4,7 +4,7 @@
 One "step" is one pass of the whole path over one Llama2-7B-shaped layer (config 2: bf16, B=1, L=4096,
 d=4096, 32 heads x 128, per-head keep ratios U[0.2, 0.9]):
     ag_gate -> ag_compact_prefill_attn (= ag_compact_kv + ag_prefill_attn over the compacted cache, sharing one
-    flag scan) -> one ag_decode_attn step.
+    launch for the flag scan and the copy) -> one ag_decode_attn step.
 `value` is prompt tokens per second through that step, inputs resident in HBM.  The same JSON line carries
   roofline      : the dominant kernel (masked prefill attention) against the bf16 MFMA peak,
   decode        : config 3 (B=32, ragged caches ~ round(4096 U[0.1,1]), Bernoulli(0.5) appends), 256 decode
@@ -89,7 +89,7 @@ def prefill_leg(args, torch, ag, W):
 
     def step():
         ag.ag_gate(ctx, x, wg, bias, wl.tau, wl.n_sink, None, flags)
-        ag.ag_compact_prefill_attn(ctx, q, k, v, pf_flags, wl.scale, 0, cache, out)   # compaction + attention, one flag scan
+        ag.ag_compact_prefill_attn(ctx, q, k, v, pf_flags, wl.scale, 0, cache, out)   # scan + compaction in one launch, then attention
         ag.ag_decode_attn(ctx, dq, dk, dv, None, L, wl.scale, cache, dout)
 
     for _ in range(args.warmup):

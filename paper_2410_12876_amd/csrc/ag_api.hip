@@ -290,9 +290,9 @@ ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void
   int32_t *blk_off = ws.take<int32_t>((size_t)units * (nw + 1));
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_compact_kv: workspace too small (need %zu)", ws.off);
   hipStream_t s = (hipStream_t)hip_stream;
-  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off, nullptr));
-  AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(cache->D * ag_dtype_size(cache->dtype)), pos0,
-                           cache->k, cache->v, cache->idx, cache->row_off, cache->len));
+  AG_HIP(ag_launch_scan_compact(ctx, s, flags, units, L, words, blk_off, nullptr, k, v,
+                                (int)(cache->D * ag_dtype_size(cache->dtype)), pos0, cache->k, cache->v, cache->idx,
+                                cache->row_off, cache->len));
   return AG_OK;
 }
 
@@ -392,13 +392,16 @@ ag_status prefill_common(ag_ctx *ctx, void *hip_stream, const void *q, const voi
   ag_status st = need_device(ctx);
   if (st != AG_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
-  AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off, tuned ? &plan : nullptr));
-  if (!cache) {
+  const ag_pf_plan *pl = tuned ? &plan : nullptr;
+  if (!cache) {  // scan and compaction in one launch, into the workspace
     AG_HIP(ag_launch_slab_offsets(s, wro, units, L));
-    AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(D * esz), 0, wk, wv, widx, wro, wlen));
-  } else if (fill_cache) {
-    AG_HIP(ag_launch_compact(ctx, s, k, v, words, blk_off, units, L, (int)(D * esz), pos0, cache->k, cache->v,
-                             cache->idx, cache->row_off, cache->len));
+    AG_HIP(ag_launch_scan_compact(ctx, s, flags, units, L, words, blk_off, pl, k, v, (int)(D * esz), 0, wk, wv, widx, wro,
+                                  wlen));
+  } else if (fill_cache) {  // ... into the caller's cache
+    AG_HIP(ag_launch_scan_compact(ctx, s, flags, units, L, words, blk_off, pl, k, v, (int)(D * esz), pos0, cache->k,
+                                  cache->v, cache->idx, cache->row_off, cache->len));
+  } else {  // the cache already holds the compacted rows
+    AG_HIP(ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off, pl));
   }
   AG_HIP(ag_launch_prefill(ctx, s, q, k, v, words, blk_off, B, L, Hq, Hkv, D, dtype, scale, n_recent, kc, vc, row_off,
                            out, plan, part));

@@ -87,9 +87,10 @@ hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags,
 // row_off[u] = u * L for u in [0, units]: one full-length slab per unit.
 hipError_t ag_launch_slab_offsets(hipStream_t s, int64_t *row_off, int units, int L);
 
-hipError_t ag_launch_compact(ag_ctx *ctx, hipStream_t s, const void *k, const void *v, const uint64_t *words,
-                             const int32_t *blk_off, int units, int L, int row_bytes, int pos0, void *kc, void *vc,
-                             int32_t *idx, const int64_t *row_off, int32_t *len);
+// The scan above and the stable compaction of the kept K/V rows in one launch (timed as the compaction).
+hipError_t ag_launch_scan_compact(ag_ctx *ctx, hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
+                                  int32_t *blk_off, const ag_pf_plan *plan, const void *k, const void *v, int row_bytes,
+                                  int pos0, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len);
 
 hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype dt, int B, int L, int d_in,
                           const void *w, const float *bias, int H_f, float thr, int n_sink, float *logits,
