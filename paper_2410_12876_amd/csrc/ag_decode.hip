@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
                                                                 const T *__restrict__ vc,
                                                                 const int64_t *__restrict__ row_off,
                                                                 const int32_t *__restrict__ len, int U, int Hkv,
-                                                                int meta_lds, float qscale,
+                                                                int meta_lds, int grid_stream, float qscale,
                                                                 int32_t *__restrict__ item_off_g,
                                                                 float *__restrict__ pm, float *__restrict__ pl,
                                                                 float *__restrict__ pacc) {
@@ -137,7 +137,12 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
     for (int u = tid; u <= U; u += 256) item_off_g[u] = item_off[u];
 
   const int grp = lane / LPR, seg = lane % LPR;
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  // The launch holds more workgroups than the streaming regime wants (grid_stream = kWgsPerCu per CU).  If every
+  // item can have a workgroup of its own, it gets one -- a small step is one round of loads instead of two; else
+  // only the first grid_stream workgroups walk the list.
+  const int n_wg = n_items <= (int)gridDim.x ? n_items : min((int)gridDim.x, grid_stream);
+  if ((int)blockIdx.x >= n_wg) return;
+  for (int item = blockIdx.x; item < n_items; item += n_wg) {
     // unit of this item: last u with item_off[u] <= item
     int lo = 0, hi = U;
     while (hi - lo > 1) {
@@ -432,7 +437,8 @@ hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new
   const size_t shmem = (size_t)(U + 1 + 256) * 4 + (size_t)NST * G * (D + 2) * 4 +
                        (meta_lds ? (size_t)U * 4 + 8 + (size_t)U * 8 : 0);
   const float qscale = scale * kLog2e;
-  int blocks = num_cu * kWgsPerCu;
+  const int grid_stream = num_cu * kWgsPerCu;
+  int blocks = 2 * grid_stream;  // the kernel uses them all only when that gives every item its own workgroup
   if (blocks > items) blocks = (int)items;
   if (blocks < 1) blocks = 1;
   if (shmem > 48 * 1024) {
@@ -442,7 +448,7 @@ hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new
   }
   ag_tick(ctx, AG_K_DECODE_PARTIAL, s);
   hipLaunchKernelGGL((ag_decode_partial_kernel<T, D, G>), dim3(blocks), dim3(256), shmem, s, (const T *)q,
-                     (const T *)kc, (const T *)vc, row_off, len, U, Hkv, meta_lds, qscale, item_off, pm, pl, pacc);
+                     (const T *)kc, (const T *)vc, row_off, len, U, Hkv, meta_lds, grid_stream, qscale, item_off, pm, pl, pacc);
   ag_tock(ctx, AG_K_DECODE_PARTIAL, s);
   ag_tick(ctx, AG_K_DECODE_MERGE, s);
   hipLaunchKernelGGL((ag_decode_merge_kernel<T, D>), dim3(B * Hq), dim3(D), 0, s, (const T *)q, (const T *)k_new,
