@@ -74,6 +74,38 @@ def test_gate_bf16_shapes(B, L, d_in, H, tau, n_sink):
     check_gate(x, w, bias, tau, n_sink, 1e-4)
 
 
+@pytest.mark.parametrize("B,L,d_in,H,misalign", [(1, 2048, 256, 4, False), (2, 1500, 512, 8, False), (1, 4100, 1024, 12, False),
+                                                  (1, 9000, 128, 20, False), (1, 2100, 2048, 32, False), (1, 2048, 256, 6, False),
+                                                  (1, 3000, 512, 8, True), (3, 3000, 4096, 32, False)])
+def test_gate_bf16_many_tokens(B, L, d_in, H, misalign):
+    """Enough tokens for the fused gate kernel: head counts that are and are not a multiple of 4 (the latter take the
+    pre-packed weights), a weight tensor that is not 16-byte aligned (also pre-packed), launches with and without
+    K splits across workgroups and with one and two workgroups per CU, twice in a row (the arrival counters must be
+    back at zero)."""
+    x = rand_t(11, (B, L, d_in), "bf16", 0.5)
+    w = rand_t(12, (d_in, H), "bf16", 1.0 / math.sqrt(d_in))
+    bias = np.random.default_rng(13).standard_normal(H).astype(np.float32) * 0.2
+    ref_logits, ref_flags = oracle.gate(x.f32, w.f32, bias, 0.5, 1)
+    near = (np.abs(ref_logits - oracle.logit_threshold(0.5)) < 1e-3).transpose(0, 2, 1)
+    ctx = make_ctx(B, L, H, H, 64, code("bf16"), d_in=d_in)
+    dw = dev(w)
+    if misalign:
+        buf = torch.zeros(d_in * H + 4, dtype=torch.bfloat16, device=DEV)
+        buf[4:].copy_(dw.reshape(-1))
+        dw = buf[4:].view(d_in, H)
+        assert dw.data_ptr() % 16 == 8
+    dx, db = dev(x), dev(bias)
+    for rep in range(2):
+        logits = torch.zeros(B, L, H, dtype=torch.float32, device=DEV)
+        flags = torch.full((B, H, L), 7, dtype=torch.uint8, device=DEV)
+        ag.ag_gate(ctx, dx, dw, db, 0.5, 1, logits, flags)
+        torch.cuda.synchronize()
+        assert np.abs(logits.cpu().numpy() - ref_logits).max() <= 1e-4
+        got = flags.cpu().numpy()
+        assert np.array_equal(got[~near], ref_flags[~near]) and set(np.unique(got)) <= {0, 1}
+    ctx.close()
+
+
 def test_gate_fp32_ragged():
     x = rand_t(4, (2, 50, 96), "f32")
     w = rand_t(5, (96, 5), "f32", 0.1)
