@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256) void ag_scan_compact_kernel(const uint8_t *__r
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
   constexpr int RPI = 64 / LPR;  // rows per wave iteration
-  constexpr int UN = 4;          // independent rows in flight per lane group
+  constexpr int UN = 8;          // independent rows in flight per lane group (8: most words need one round of loads)
   const int sub = lane / LPR, seg0 = lane % LPR;
   const size_t src_unit = (size_t)u * L * row_vec;
   // Loads are unconditional (a row index past the word's last kept row re-reads that last row) so that all UN row
