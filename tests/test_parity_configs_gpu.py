@@ -639,3 +639,40 @@ def test_project_compact_kv_feeds_the_prefill():
     ref = oracle.prefill_attn(q.f32, host_f32(kv[0]), host_f32(kv[1]), flags, 1 / math.sqrt(D))
     assert attn_error("bf16", host_f32(o1), ref) <= attn_tolerance("bf16", ref)
     ctx.close()
+
+
+# ------------------------------------------------------------------ the benchmark's step, at full size
+def test_config2_full_size_step_as_the_benchmark_runs_it():
+    """ag_gate -> ag_compact_prefill_attn -> ag_decode_attn on the whole Llama2-7B-shaped layer (config 2), the calls
+    and launch shapes that bench.py times: flags against the oracle's gate (logits within 1e-3 of the threshold
+    excluded and counted), the cache bit for bit against the oracle's compaction of the flags the GPU produced,
+    sampled query rows of every head against the definition, one decode step against the oracle on that cache."""
+    wl = W.config2()
+    B, L, Hq, Hkv, D, d = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D, wl.d_model
+    U, cap = B * Hkv, L + 8
+    ro = oracle.slab_row_off(U, cap)
+    ctx = make_ctx(B, L, Hq, Hkv, D, ag.AG_BF16, d_in=d, cache_rows=U * cap)
+    cache = new_cache(B, Hkv, D, torch.bfloat16, ro)
+    flags = torch.empty(B, Hkv, L, dtype=torch.uint8, device=DEV)
+    dq, dk, dv = dev(wl.q), dev(wl.k), dev(wl.v)
+    out = torch.empty_like(dq)
+    ag.ag_gate(ctx, dev(wl.x), dev(wl.w_gate), dev(wl.bias), wl.tau, wl.n_sink, None, flags)
+    ag.ag_compact_prefill_attn(ctx, dq, dk, dv, flags, wl.scale, 0, cache, out)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    got_flags = flags.cpu().numpy()
+    ref_logits, ref_flags = oracle.gate(wl.x.f32, wl.w_gate.f32, wl.bias, wl.tau, wl.n_sink)
+    near = (np.abs(ref_logits - oracle.logit_threshold(wl.tau)) < 1e-3).transpose(0, 2, 1)
+    assert np.array_equal(got_flags[~near], ref_flags[~near])
+    ref, over = oracle.compact_kv(wl.k.storage, wl.v.storage, got_flags, ro)
+    assert over == 0 and np.array_equal(cache.len.cpu().numpy(), ref.len)
+    gk, gv, gi = host_bits(cache.k), host_bits(cache.v), cache.idx.cpu().numpy()
+    for u in range(U):
+        a, n = int(ro[u]), int(ref.len[u])
+        assert np.array_equal(gk[a:a + n], ref.k[a:a + n]) and np.array_equal(gv[a:a + n], ref.v[a:a + n])
+        assert np.array_equal(gi[a:a + n], ref.idx[a:a + n])
+    check_sampled_rows(host_f32(out), wl.q, wl.k, wl.v, got_flags, wl.scale, sample_rows(L, 77), "cfg2 step")
+    decode_and_check(ctx, wl, cache, ref, ro, 1, 78, None)
+    print("cfg2 step: %d of %d logits within 1e-3 of the threshold, %d flags differ there" %
+          (int(near.sum()), near.size, int((got_flags != ref_flags).sum())))
+    ctx.close()
