@@ -19,14 +19,14 @@
 //   * Small launches (one 4096-token layer is ~1000 workgroups of very different length) are bounded by
 //     their longest workgroup, the last query tile of the head that keeps most.  There the key range of a
 //     (head, query tile) item is cut into chunks of at most `chunk_tiles` tiles, one workgroup per chunk;
-//     chunk_tiles is the average number of tiles per workgroup slot, measured on the device from the flags, so
-//     only an item that alone exceeds the average is cut.  Items that fit one chunk write their output
+//     chunk_tiles is a little above the average number of tiles per workgroup slot, measured on the device from
+//     the flags, so only an item that alone exceeds it is cut.  Items that fit one chunk write their output
 //     directly; the few long ones store unnormalised fp32 partial states in the workspace, and the chunk that
 //     arrives last (a per-item counter) combines them with its own registers and writes the rows.
 //   * Workgroups go to the 8 XCDs, and inside an XCD to its 4 shader engines, round-robin by their index
 //     (measured: workgroup i runs on XCD i % 8, engine (i / 8) % 4), so the index -> (head, query tile) map
 //     decides both L2 locality and balance.  All tiles of one head are given to one XCD (its K/V stay in that
-//     XCD's L2), longest first; a small kernel (ag_prefill_order_kernel) first deals the heads to the XCDs in
+//     XCD's L2), longest first; the flag scan's last workgroup first deals the heads to the XCDs in
 //     snake order of their kept-row counts, and the heads of an XCD rotate over its engines from one query tile
 //     to the next, so every engine gets about the same number of key tiles although heads keep 20 % to 90 %.
 #include <string.h>
