@@ -165,6 +165,24 @@ def test_compact_bit_exact(dtype, B, H, L, D, keep):
     check_compact(k, v, flags, L, pos0=17)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_compact_shape_sweep(seed):
+    """Seeded sweep over the scan + compaction launch: ragged lengths (word, 256-token-group and 4-byte alignment of a
+    unit's flags all vary), both dtypes and head sizes, keep ratios from nothing to everything per head, and slabs
+    that are sometimes too small (surplus rows dropped and reported)."""
+    g = np.random.default_rng(500 + seed)
+    dtype = "f32" if seed % 3 == 2 else "bf16"
+    D = int(g.choice([64, 128]))
+    B, H = int(g.integers(1, 4)), int(g.integers(1, 6))
+    L = int(g.choice([1, 3, 63, 64, 65, 255, 256, 257, 511, 1000, 1023, 1025, 2050, 3001]))
+    keep = g.choice([0.0, 0.05, 0.3, 0.5, 0.8, 1.0], size=(B, H, 1))
+    flags = (g.random((B, H, L)) < keep).astype(np.uint8) * np.uint8(g.choice([1, 255]))
+    k, v = rand_t(600 + seed, (B, H, L, D), dtype), rand_t(700 + seed, (B, H, L, D), dtype)
+    most = int((flags != 0).reshape(B * H, L).sum(1).max())
+    cap = L if seed % 4 else max(1, most - int(g.integers(0, max(2, most // 3))))
+    check_compact(k, v, flags, cap, pos0=int(g.integers(0, 100)))
+
+
 def test_compact_all_evicted_all_kept_and_overflow():
     B, H, L, D = 1, 3, 300, 128
     k, v = rand_t(9, (B, H, L, D), "bf16"), rand_t(10, (B, H, L, D), "bf16")
