@@ -259,6 +259,27 @@ def test_prefill_fully_evicted_head_returns_own_value_and_all_kept_is_causal(dty
     assert attn_error(dtype, got[:, 1:2], ref) <= attn_tolerance(dtype, ref)
 
 
+@pytest.mark.parametrize("dtype,D,scale_mult,offset", [("bf16", 128, 8.0, 0.0), ("bf16", 128, 1.0, 300.0), ("bf16", 64, 6.0, 0.0),
+                                                       ("f32", 64, 3.0, 0.0)])
+def test_prefill_sharp_and_shifted_scores(dtype, D, scale_mult, offset):
+    """Scores whose row maximum jumps by far more than the kernel's lazy-rescale gap from tile to tile (a scale 6 to 8
+    times 1/sqrt(D): nearly one-hot softmax rows), and scores shifted by a large common offset (a constant
+    component in q and k: every score near +300, differences of order one) -- the running maximum must absorb both.
+    (fp32 only with moderate magnitudes: its 1e-5 bound cannot hold once the scores themselves, computed in fp32,
+    are hundreds -- one unit in the last place of a score of 400 is already 3e-5.)"""
+    B, H, L = 1, 2, 700
+    g = np.random.default_rng(int(D + 10 * scale_mult + offset))
+    qf, kf = g.standard_normal((B, H, L, D)), g.standard_normal((B, H, L, D))
+    if offset:
+        qf[..., 0] = math.sqrt(offset * math.sqrt(D))
+        kf[..., 0] = math.sqrt(offset * math.sqrt(D))
+    q, k = W.store(qf.astype(np.float32), dtype), W.store(kf.astype(np.float32), dtype)
+    v = rand_t(41, (B, H, L, D), dtype)
+    flags = rand_flags(42, (B, H, L), 0.5)
+    check_prefill(q, k, v, flags, scale_mult / math.sqrt(D))
+    check_prefill(q, k, v, flags, scale_mult / math.sqrt(D), with_cache=False)
+
+
 def test_prefill_poisoned_evicted_rows_do_not_leak():
     """NaN in the K/V rows of evicted tokens must not reach any kept token's output row."""
     B, H, L, D = 1, 2, 200, 128
