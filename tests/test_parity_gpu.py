@@ -362,6 +362,40 @@ def test_decode_ragged_shapes(dtype, B, Hq, Hkv, D, max_len):
     check_decode(wl, 6, 0.5, dtype)
 
 
+@pytest.mark.parametrize("G,scale_mult", [(1, 8.0), (4, 6.0), (2, 1.0)])
+def test_decode_sharp_and_shifted_scores(G, scale_mult):
+    """Decode rows that are nearly one-hot (a scale several times 1/sqrt(D)) and, for the last case, scores with a
+    large common offset (cache keys and queries share a constant component): the per-lane-group running maxima and
+    the merges of their states must absorb both."""
+    B, Hkv, D, steps = 2, 2, 128, 3
+    g = np.random.default_rng(int(10 * scale_mult) + G)
+    len0 = np.array([900, 130, 257, 1], np.int32)
+    wl = W.decode_batch(33, "t", "bf16", B, Hkv * G, Hkv, D, len0, steps, pos0=1000)
+    shift = scale_mult == 1.0
+    if shift:  # every key of the cache gets the same large first component
+        kf = wl.k_cache.f32.copy()
+        kf[:, 0] = 60.0
+        wl.k_cache = W.store(kf, "bf16")
+    wl.scale = scale_mult / math.sqrt(D)
+    ctx = make_ctx(B, 1, wl.Hq, Hkv, D, ag.AG_BF16, cache_rows=int(wl.row_off[-1]))
+    cache = cache_from_host(B, Hkv, D, wl.k_cache, wl.v_cache, wl.idx, wl.row_off, wl.len0)
+    ref = oracle.Cache(wl.k_cache.f32.copy(), wl.v_cache.f32.copy(), wl.idx.copy(), wl.row_off.copy(), wl.len0.copy())
+    out = torch.empty(B, wl.Hq, D, dtype=torch.bfloat16, device=DEV)
+    for s in range(steps):
+        q, kn, vn, nf = wl.step_inputs(s, 0.5)
+        if shift:
+            qf, knf = q.f32.copy(), kn.f32.copy()
+            qf[..., 0] = 60.0
+            knf[..., 0] = 60.0
+            q, kn = W.store(qf, "bf16"), W.store(knf, "bf16")
+        ag.ag_decode_attn(ctx, dev(q), dev(kn), dev(vn), dev(nf), wl.pos0 + s, wl.scale, cache, out)
+        want, dropped = oracle.decode_step(q.f32, kn.f32, vn.f32, nf, wl.pos0 + s, ref, wl.scale)
+        got = host_f32(out)
+        assert dropped == 0 and np.isfinite(got).all()
+        assert attn_error("bf16", got, want) <= attn_tolerance("bf16", want), "step %d" % s
+    ctx.close()
+
+
 def test_decode_empty_cache_returns_new_value_exactly_and_overflow_is_dropped():
     B, H, D = 1, 2, 128
     wl = W.decode_batch(31, "t", "bf16", B, H, H, D, np.array([0, 3], np.int32), 1, pos0=10)
