@@ -93,9 +93,11 @@ size_t ag_workspace_bytes(int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, 
 ag_status ag_poll_error(ag_ctx *ctx, void *hip_stream);
 
 /*
- * Kernel timing for benchmarks.  While enabled, every kernel the library launches is bracketed by a pair of
- * HIP events on the call's stream (up to 1024 launches per kernel id are remembered; later ones are not
- * timed).  ag_timing_enable(ctx, 1) resets the counts; ag_timing_read waits for the recorded events and
+ * Kernel timing for benchmarks.  While enabled, every kernel the library launches carries a pair of HIP events
+ * on the call's stream: the main kernels (fused gate, scan + compaction, prefill, decode partial and merge,
+ * projection) have them attached to the launch itself, so the duration is the kernel's own; the remaining
+ * launches are bracketed by records on the stream.  Up to 1024 launches per kernel id are remembered; later
+ * ones are not timed.  Leave timing off while the stream is being captured into a HIP graph.  ag_timing_enable(ctx, 1) resets the counts; ag_timing_read waits for the recorded events and
  * returns the summed duration and the number of launches of one kernel id in [0, ag_timing_kernels()).
  * Ids: 0 gate (GEMM), 1 gate_finalize, 2 flag_scan, 3 compact, 4 prefill, 5 decode_partial, 6 decode_merge.
  */

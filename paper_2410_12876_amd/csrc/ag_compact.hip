@@ -288,10 +288,8 @@ hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags,
   ag_pf_plan none;
   memset(&none, 0, sizeof(none));
   int32_t *arrivals = ctx->d_err + 16;  // zeroed at creation; the kernel leaves it at zero
-  ag_tick(ctx, AG_K_FLAG_SCAN, s);
-  hipLaunchKernelGGL(ag_flag_scan_kernel, dim3((nw + kSegWords - 1) / kSegWords, units), dim3(kScanThreads), 0, s, flags,
-                     L, nw, words, blk_off, plan ? *plan : none, units, arrivals);
-  ag_tock(ctx, AG_K_FLAG_SCAN, s);
+  AG_LAUNCH(ag_time_kernel(ctx, AG_K_FLAG_SCAN), ag_flag_scan_kernel, dim3((nw + kSegWords - 1) / kSegWords, units),
+            dim3(kScanThreads), 0, s, flags, L, nw, words, blk_off, plan ? *plan : none, units, arrivals);
   return hipGetLastError();
 }
 
@@ -305,15 +303,14 @@ hipError_t ag_launch_scan_compact(ag_ctx *ctx, hipStream_t s, const uint8_t *fla
   int32_t *arrivals = ctx->d_err + 16;  // zeroed at creation; the kernel leaves it at zero
   const dim3 grid((nw + 3) / 4, units), block(256);
 #define AG_SC(LPR)                                                                                                  \
-  hipLaunchKernelGGL(ag_scan_compact_kernel<LPR>, grid, block, 0, s, flags, L, nw, words, blk_off, plan ? *plan : none, \
+  AG_LAUNCH(ev, ag_scan_compact_kernel<LPR>, grid, block, 0, s, flags, L, nw, words, blk_off, plan ? *plan : none, \
                      units, arrivals, (const uint4 *)k, (const uint4 *)v, row_vec, pos0, (uint4 *)kc, (uint4 *)vc, idx, \
                      row_off, len, ctx->d_err)
-  ag_tick(ctx, AG_K_COMPACT, s);
+  const ag_evpair ev = ag_time_kernel(ctx, AG_K_COMPACT);
   if (row_vec <= 8) AG_SC(8);
   else if (row_vec <= 16) AG_SC(16);
   else if (row_vec <= 32) AG_SC(32);
   else AG_SC(64);
 #undef AG_SC
-  ag_tock(ctx, AG_K_COMPACT, s);
   return hipGetLastError();
 }

@@ -446,15 +446,11 @@ hipError_t launch_t(ag_ctx *ctx, hipStream_t s, const void *q, const void *k_new
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
   }
-  ag_tick(ctx, AG_K_DECODE_PARTIAL, s);
-  hipLaunchKernelGGL((ag_decode_partial_kernel<T, D, G>), dim3(blocks), dim3(256), shmem, s, (const T *)q,
+  AG_LAUNCH(ag_time_kernel(ctx, AG_K_DECODE_PARTIAL), (ag_decode_partial_kernel<T, D, G>), dim3(blocks), dim3(256), shmem, s, (const T *)q,
                      (const T *)kc, (const T *)vc, row_off, len, U, Hkv, meta_lds, grid_stream, qscale, item_off, pm, pl, pacc);
-  ag_tock(ctx, AG_K_DECODE_PARTIAL, s);
-  ag_tick(ctx, AG_K_DECODE_MERGE, s);
-  hipLaunchKernelGGL((ag_decode_merge_kernel<T, D>), dim3(B * Hq), dim3(D), 0, s, (const T *)q, (const T *)k_new,
+  AG_LAUNCH(ag_time_kernel(ctx, AG_K_DECODE_MERGE), (ag_decode_merge_kernel<T, D>), dim3(B * Hq), dim3(D), 0, s, (const T *)q, (const T *)k_new,
                      (const T *)v_new, new_flags, pos, Hq, Hkv, qscale, item_off, pm, pl, pacc, (T *)kc, (T *)vc, idx,
                      row_off, len, (T *)out, d_err, ring);
-  ag_tock(ctx, AG_K_DECODE_MERGE, s);
   return hipGetLastError();
 }
 

@@ -363,13 +363,13 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
     }
     if (fused) {
       const dim3 grid((unsigned)tiles32, fsplits), block(64 * kFusedWaves);
-      ag_tick(ctx, AG_K_GATE, s);
+      const ag_evpair ev = ag_time_kernel(ctx, AG_K_GATE);
       // PF = feature chunks a wave keeps in flight.  A launch of at most one workgroup per CU is one round of loads
       // per wave (PF = 4); a longer one runs two workgroups per CU with half the registers (PF = 2), so that one
       // loads while the other reduces and writes its flags.
       const bool two_per_cu = (int64_t)tiles32 * fsplits > ctx->num_cu;
 #define AG_GATE_FUSED(RAWV, PFV, WPTR)                                                                             \
-  hipLaunchKernelGGL((ag_gate_fused_kernel<RAWV, PFV>), grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)(WPTR), \
+  AG_LAUNCH(ev, (ag_gate_fused_kernel<RAWV, PFV>), grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)(WPTR), \
                      tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags, partial, tickets)
       if (raw_w) {
         if (two_per_cu) AG_GATE_FUSED(true, 2, w); else AG_GATE_FUSED(true, 4, w);
@@ -377,7 +377,6 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
         AG_GATE_FUSED(false, 4, wp);  // measured: the pre-packed path is slower with two workgroups per CU
       }
 #undef AG_GATE_FUSED
-      ag_tock(ctx, AG_K_GATE, s);
       return hipGetLastError();
     }
     const dim3 grid(p.tiles, p.splits);

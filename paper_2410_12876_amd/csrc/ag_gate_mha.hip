@@ -256,10 +256,9 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
   ag_prefill_d128_plan(ctx->num_cu, B, L, hp, hp, ws, &plan, &part);
   if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
 
-  ag_tick(ctx, AG_K_MHA_PROJ, s);
-  hipLaunchKernelGGL(ag_proj_gemm_kernel<false>, dim3(N / kBNc, (unsigned)((tokens + kBM - 1) / kBM)), dim3(256), 0, s,
-                     (const uint16_t *)x, (const uint16_t *)w_qkv, tokens, d_model, N, L, hp, qkv, ag_proj_compact{});
-  ag_tock(ctx, AG_K_MHA_PROJ, s);
+  AG_LAUNCH(ag_time_kernel(ctx, AG_K_MHA_PROJ), ag_proj_gemm_kernel<false>,
+            dim3(N / kBNc, (unsigned)((tokens + kBM - 1) / kBM)), dim3(256), 0, s, (const uint16_t *)x,
+            (const uint16_t *)w_qkv, tokens, d_model, N, L, hp, qkv, ag_proj_compact{});
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t nf = (size_t)units * L;
@@ -267,10 +266,9 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
   if ((e = ag_launch_flag_scan(ctx, s, ones, units, L, words, blk_off, &plan)) != hipSuccess) return e;
   if ((e = ag_launch_slab_offsets(s, row_off, units, L)) != hipSuccess) return e;
   // every flag is set, so the compacted rows of a head are its K', V' rows themselves
-  ag_tick(ctx, AG_K_MHA_ATTN, s);
   e = ag_launch_prefill_d128(s, qkv, qkv + per, qkv + 2 * per, words, blk_off, B, L, hp, hp, scale * 1.4426950408889634f,
-                             1, qkv + per, qkv + 2 * per, row_off, feat, plan, part, /*out_token_major=*/true);
-  ag_tock(ctx, AG_K_MHA_ATTN, s);
+                             1, qkv + per, qkv + 2 * per, row_off, feat, plan, part, /*out_token_major=*/true,
+                             ag_time_kernel(ctx, AG_K_MHA_ATTN));
   if (e != hipSuccess) return e;
   return ag_launch_gate(ctx, s, feat, AG_BF16, B, L, hp * kDh, w_o, bias, H_f, thr, n_sink, logits, flags, ws);
 }
@@ -293,9 +291,8 @@ hipError_t ag_launch_project_compact(ag_ctx *ctx, hipStream_t s, const void *x, 
   hipError_t e = ag_launch_flag_scan(ctx, s, flags, units, L, words, blk_off, nullptr);
   if (e != hipSuccess) return e;
   const ag_proj_compact cp{words, blk_off, row_off, (uint16_t *)kc, (uint16_t *)vc, idx, len, ctx->d_err, nw, pos0};
-  ag_tick(ctx, AG_K_MHA_PROJ, s);
-  hipLaunchKernelGGL(ag_proj_gemm_kernel<true>, dim3(N / kBNc, (unsigned)((tokens + kBM - 1) / kBM)), dim3(256), 0, s,
-                     (const uint16_t *)x, (const uint16_t *)w_kv, tokens, d_model, N, L, Hkv, (uint16_t *)kv_out, cp);
-  ag_tock(ctx, AG_K_MHA_PROJ, s);
+  AG_LAUNCH(ag_time_kernel(ctx, AG_K_MHA_PROJ), ag_proj_gemm_kernel<true>,
+            dim3(N / kBNc, (unsigned)((tokens + kBM - 1) / kBM)), dim3(256), 0, s, (const uint16_t *)x,
+            (const uint16_t *)w_kv, tokens, d_model, N, L, Hkv, (uint16_t *)kv_out, cp);
   return hipGetLastError();
 }

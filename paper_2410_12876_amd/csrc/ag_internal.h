@@ -1,5 +1,6 @@
 // Internal declarations shared by the libag translation units (not part of the C ABI).
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -39,6 +40,30 @@ static inline void ag_tock(ag_ctx *ctx, int id, hipStream_t s) {
     ctx->timers[id].n++;
   }
 }
+
+// Events attached to ONE kernel launch (hipExtLaunchKernelGGL records them right at the kernel's start and end, so
+// the duration is the kernel's own, without the few microseconds an event pair around a launch adds).  Both are
+// null when timing is off or the slots are used up; AG_LAUNCH then launches the ordinary way.
+struct ag_evpair {
+  hipEvent_t start, stop;
+};
+static inline ag_evpair ag_time_kernel(ag_ctx *ctx, int id) {
+  ag_evpair e{nullptr, nullptr};
+  if (ctx && ctx->timing && ctx->timers[id].n < kTimerSlots) {
+    e.start = ctx->timers[id].start[ctx->timers[id].n];
+    e.stop = ctx->timers[id].stop[ctx->timers[id].n];
+    ctx->timers[id].n++;
+  }
+  return e;
+}
+#define AG_LAUNCH(ev, kernel, grid, block, shmem, stream, ...)                                              \
+  do {                                                                                                      \
+    const ag_evpair ev_ = (ev); /* evaluated once: taking a pair uses up a timer slot */                    \
+    if (ev_.start)                                                                                          \
+      hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, ev_.start, ev_.stop, 0, __VA_ARGS__);       \
+    else                                                                                                    \
+      hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                  \
+  } while (0)
 
 // Bump allocator over the context's workspace; every block is 256-byte aligned.
 struct ws_cursor {
@@ -107,7 +132,8 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
                                   const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
                                   const void *kc, const void *vc, const int64_t *row_off, void *out,
-                                  const ag_pf_plan &plan, float *part, bool out_token_major = false);
+                                  const ag_pf_plan &plan, float *part, bool out_token_major = false,
+                                  ag_evpair ev = ag_evpair{nullptr, nullptr});
 
 // The paper's main gate: MHA' (projection GEMM, causal attention with hp heads of 128) in front of ag_launch_gate.
 size_t ag_ws_gate_mha_bytes(int B, int L, int d_model, int hp, int H_f);

@@ -341,15 +341,12 @@ hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const vo
                              ag_dtype dt, float scale, int n_recent, const void *kc, const void *vc,
                              const int64_t *row_off, void *out, const ag_pf_plan &plan, float *part) {
   const int nw = ag_nwords(L);
-  ag_tick(ctx, AG_K_PREFILL, s);
   const int G = Hq / Hkv;
   const float qscale = scale * kLog2e;
-  if (dt == AG_BF16 && D == 128) {
-    const hipError_t e = ag_launch_prefill_d128(s, q, k, v, words, blk_off, B, L, Hq, Hkv, qscale, n_recent, kc, vc,
-                                                row_off, out, plan, part);
-    ag_tock(ctx, AG_K_PREFILL, s);
-    return e;
-  }
+  if (dt == AG_BF16 && D == 128)
+    return ag_launch_prefill_d128(s, q, k, v, words, blk_off, B, L, Hq, Hkv, qscale, n_recent, kc, vc, row_off, out, plan,
+                                  part, false, ag_time_kernel(ctx, AG_K_PREFILL));
+  ag_tick(ctx, AG_K_PREFILL, s);
   if (dt == AG_BF16) {
     const int GB = G >= 4 ? 4 : G;
     const int BM = 32 * (4 / GB);

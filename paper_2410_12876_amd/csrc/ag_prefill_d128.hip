@@ -646,7 +646,7 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
 hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
                                   const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
                                   const void *kc, const void *vc, const int64_t *row_off, void *out,
-                                  const ag_pf_plan &plan, float *part, bool out_token_major) {
+                                  const ag_pf_plan &plan, float *part, bool out_token_major, ag_evpair ev) {
   (void)B;
   const int nw = ag_nwords(L);
   const int G = Hq / Hkv;
@@ -657,7 +657,7 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
   const dim3 grid((unsigned)blocks), block(64 * plan.NW);
 #define AG_PF(GG, BB) AG_PFN(GG, BB, 4)
 #define AG_PFN(GG, BB, NN)                                                                                          \
-  hipLaunchKernelGGL((ag_prefill_d128_kernel<GG, BB, NN>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k, \
+  AG_LAUNCH(ev, (ag_prefill_d128_kernel<GG, BB, NN>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k, \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
                      Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, n_recent, plan.order,               \
                      plan.head_major, (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)

@@ -641,6 +641,51 @@ def test_project_compact_kv_feeds_the_prefill():
     ctx.close()
 
 
+# ------------------------------------------------------------------------------------------ kernel timing
+def test_kernel_timing_counts_launches_and_leaves_results_alone():
+    """With timing on, the step's kernels each report the launches made and a duration that is positive and below
+    the wall-clock time of the timed region; the outputs are the bits of the untimed run."""
+    import time
+    wl = W.config2(L=2048)                                            # long enough for the fused gate kernel
+    B, L, Hq, Hkv, D, d = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D, wl.d_model
+    U, cap = B * Hkv, L + 8
+    ro = oracle.slab_row_off(U, cap)
+    dq, dk, dv, dx, dw, db = dev(wl.q), dev(wl.k), dev(wl.v), dev(wl.x), dev(wl.w_gate), dev(wl.bias)
+    g = np.random.default_rng(91)
+    q1 = dev(W.store(g.standard_normal((B, Hq, D)).astype(np.float32), "bf16"))
+    k1 = dev(W.store(g.standard_normal((B, Hkv, D)).astype(np.float32), "bf16"))
+    v1 = dev(W.store(g.standard_normal((B, Hkv, D)).astype(np.float32), "bf16"))
+    keep1 = torch.ones(B, Hkv, dtype=torch.uint8, device=DEV)
+    res, steps = [], 3
+    for timed in (False, True):
+        ctx = make_ctx(B, L, Hq, Hkv, D, ag.AG_BF16, d_in=d, cache_rows=U * cap)
+        flags = torch.empty(B, Hkv, L, dtype=torch.uint8, device=DEV)
+        out, o1 = torch.empty_like(dq), torch.empty_like(q1)
+        ctx.timing_enable(timed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            cache = new_cache(B, Hkv, D, torch.bfloat16, ro)
+            ag.ag_gate(ctx, dx, dw, db, wl.tau, wl.n_sink, None, flags)
+            ag.ag_compact_prefill_attn(ctx, dq, dk, dv, flags, wl.scale, 0, cache, out)
+            ag.ag_decode_attn(ctx, q1, k1, v1, keep1, L, wl.scale, cache, o1)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        if timed:
+            times = ctx.timing_read()
+            for name in ("gate", "compact", "prefill", "decode_partial", "decode_merge"):
+                ms, n = times[name]
+                assert n == steps, (name, n)
+                assert 0.0 < ms < wall_ms, (name, ms, wall_ms)
+            ctx.timing_enable(True)                                   # enabling again clears the counts
+            assert all(n == 0 for _, n in ctx.timing_read().values())
+        ctx.poll_error()
+        res.append((flags, out, o1, cache.len.clone()))
+        ctx.close()
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------ the benchmark's step, at full size
 def test_config2_full_size_step_as_the_benchmark_runs_it():
     """ag_gate -> ag_compact_prefill_attn -> ag_decode_attn on the whole Llama2-7B-shaped layer (config 2), the calls
