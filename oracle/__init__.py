@@ -107,6 +107,29 @@ def gate_mha(x, w_qkv, h_prime: int, d_prime: int, w_o, bias, tau: float, n_sink
     return gate(feat, w_o, bias, tau, n_sink)
 
 
+def rmsnorm(h, g, eps: float, store=None):
+    """Root-mean-square normalisation of the hidden states, the step that precedes the attention block (and with it
+    the gate of Eq. 3, whose input X is the block's input) in the decoder models of Sec. 4.  The paper does not
+    restate it; this is the definition those models use:
+        x[b,t,c] = h[b,t,c] / sqrt( (1/d) sum_c' h[b,t,c']^2 + eps ) * g[c]
+    h [B,L,d], g [d]; arithmetic in fp64; `store` names the dtype x is then held in ("bf16" rounds to nearest even,
+    None = exact).  Returns x f64 [B,L,d]."""
+    h, g = np.asarray(_f32(h), dtype=np.float64), np.asarray(_f32(g), dtype=np.float64)
+    assert h.ndim == 3 and g.shape == (h.shape[2],) and eps > 0.0
+    ms = np.empty(h.shape[:2], dtype=np.float64)
+    for b in range(h.shape[0]):
+        for t in range(h.shape[1]):
+            ms[b, t] = np.sum(h[b, t] * h[b, t]) / h.shape[2]
+    return _round_to(h / np.sqrt(ms + eps)[:, :, None] * g[None, None, :], store)
+
+
+def rmsnorm_gate(h, g, eps: float, w, bias, tau: float, n_sink: int = 0, store=None):
+    """rmsnorm, then the gate (Eq. 3, Eq. 4) on the stored x.  Returns (x, logits, flags)."""
+    x = rmsnorm(h, g, eps, store)
+    logits, flags = gate(x, w, bias, tau, n_sink)  # (gate reads its features as fp32: exact for a stored x)
+    return x, logits, flags
+
+
 def project_kv(x, w_kv, Hkv: int, D: int, store=None):
     """The layer's own key/value projection (Eq. 2: K_i = X W_i^K, V_i = X W_i^V) in the layout the path consumes.
 

@@ -453,3 +453,54 @@ def test_project_kv_matches_per_element_sums_and_rounds_to_bf16_on_request():
     bits = kb.astype(np.float32).view(np.uint32)
     assert np.all(bits & 0xffff == 0)                       # representable in bf16
     assert np.all(np.abs(kb - k) <= np.abs(k) * 2.0 ** -8)  # and the nearest such value (half a spacing at most)
+
+
+# ------------------------------------------------------------------ normalisation ahead of the gate
+def test_rmsnorm_closed_forms():
+    """Rows with a known answer: a constant row c gives sign(c) g / sqrt(1 + eps / c^2); a one-hot row a e_k gives
+    sign(a) sqrt(d) g_k at k and 0 elsewhere as eps -> 0 (the mean is over all d features, not a sum and not over the
+    non-zero ones); with g = 1 the mean square of an output row is ms / (ms + eps)."""
+    d = 12
+    g = rnd(81, d) + 2.0
+    eps = 1e-3
+    h = np.zeros((1, 3, d), np.float32)
+    h[0, 0] = -3.0
+    h[0, 1, 5] = 2.5
+    h[0, 2] = rnd(82, d)
+    x = oracle.rmsnorm(h, g, eps)
+    assert np.allclose(x[0, 0], -g.astype(np.float64) / np.sqrt(1.0 + eps / 9.0), rtol=1e-12)
+    want = np.zeros(d)
+    want[5] = float(g[5]) * 2.5 / np.sqrt(2.5 ** 2 / d + eps)
+    assert np.allclose(x[0, 1], want, rtol=1e-12) and abs(want[5] / (np.sqrt(d) * g[5]) - 1.0) < 1e-3
+    x1 = oracle.rmsnorm(h, np.ones(d, np.float32), eps)
+    ms = float(np.mean(h[0, 2].astype(np.float64) ** 2))
+    assert abs(np.mean(x1[0, 2] ** 2) - ms / (ms + eps)) < 1e-12
+
+
+def test_rmsnorm_is_scale_invariant_and_matches_the_library_routine():
+    B, L, d = 2, 7, 64
+    h, g = rnd(83, B, L, d), rnd(84, d)
+    x = oracle.rmsnorm(h, g, 1e-5)
+    assert np.allclose(oracle.rmsnorm(4.0 * h, g, 16.0 * 1e-5), x, rtol=1e-12, atol=0)   # h -> a h, eps -> a^2 eps
+    lib = torch.nn.functional.rms_norm(torch.from_numpy(h.astype(np.float64)), (d,),
+                                       torch.from_numpy(g.astype(np.float64)), eps=1e-5).numpy()
+    assert np.allclose(x, lib, rtol=1e-12, atol=1e-15)
+    xb = oracle.rmsnorm(h, g, 1e-5, store="bf16")
+    assert np.all(xb.astype(np.float32).view(np.uint32) & 0xffff == 0)
+    assert np.all(np.abs(xb - x) <= np.abs(x) * 2.0 ** -8)
+
+
+def test_rmsnorm_gate_is_the_gate_of_the_stored_x():
+    """A gate weight that reads out feature c (bias 0, tau 1/2) keeps a token iff x_c > 0, i.e. iff h_c g_c > 0: the
+    normalisation never changes a sign; the logits are those of the gate applied to the x that is returned."""
+    B, L, d = 1, 40, 16
+    h, g = rnd(85, B, L, d), rnd(86, d)
+    w = np.zeros((d, 4), np.float32)
+    for j, c in enumerate((0, 3, 7, 15)):
+        w[c, j] = 1.0
+    x, logits, flags = oracle.rmsnorm_gate(h, g, 1e-6, w, np.zeros(4, np.float32), 0.5, 0, store="bf16")
+    for j, c in enumerate((0, 3, 7, 15)):
+        assert np.array_equal(flags[0, j], (h[0, :, c] * g[c] > 0).astype(np.uint8))
+        assert np.array_equal(logits[0, :, j], x[0, :, c])
+    l2, f2 = oracle.gate(x, w, np.zeros(4, np.float32), 0.5, 0)
+    assert np.array_equal(l2, logits) and np.array_equal(f2, flags)
