@@ -16,7 +16,8 @@ kernel on the launch stream (ag_timing_* of the C ABI) over the same number of s
   machine       : what this machine sustains (MFMA loop, streaming copy, vendor bf16 GEMM) beside the data-sheet peaks.
 Optional legs: --config 4 / --config 5 --layer l (the other layer workloads), --keep, --seq-len, --decode-stack
 (config 5's decode phase: one token through 32 layers, eager and from a HIP graph), --project (the K/V projection
-with the compaction in its epilogue), next_layer_gate_overlap (the next layer's gate on a second stream).
+with the compaction in its epilogue), --norm-gate (the gate fused with the normalisation of its input),
+next_layer_gate_overlap (the next layer's gate on a second stream).
 """
 import argparse
 import json
@@ -334,6 +335,54 @@ def projection_leg(args, torch, ag, W, wl):
             "tflops": flops / (proj_ms * 1e-3) / 1e12, "separate_compaction_ms": t["compact"][0] / t["compact"][1]}
 
 
+def norm_gate_leg(args, torch, ag, W, wl):
+    """The gate fused with the RMS normalisation that produces its input (ag_rmsnorm_gate) on the headline shape,
+    beside the two separate passes it replaces: the framework's own rms_norm kernel, then ag_gate.  The residual
+    stream h is the layer's x scaled by 3 (the normalisation removes the scale); weights 1 + 0.1 N(0, 1)."""
+    B, L, d, H = wl.B, wl.L, wl.d_model, wl.Hkv
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    h = (to_dev(wl.x, torch).float() * 3.0).to(torch.bfloat16)
+    g = (1.0 + 0.1 * torch.randn(d, device="cuda", generator=gen)).to(torch.bfloat16)
+    wg, bias = to_dev(wl.w_gate, torch), torch.from_numpy(wl.bias).cuda()
+    x = torch.empty_like(h)
+    flags = torch.empty(B, H, L, dtype=torch.uint8, device="cuda")
+    ctx = ag.Context(0, ag.workspace_bytes(B, L, H, H, wl.D, ag.AG_BF16, d, 0))
+    n = 20
+
+    def fused():
+        ag.ag_rmsnorm_gate(ctx, h, g, 1e-5, wg, bias, wl.tau, wl.n_sink, x, None, flags)
+
+    def separate():
+        y = torch.nn.functional.rms_norm(h, (d,), g, 1e-5)
+        ag.ag_gate(ctx, y, wg, bias, wl.tau, wl.n_sink, None, flags)
+
+    def wall(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e3
+
+    fused_ms, sep_ms = wall(fused), wall(separate)
+    ctx.timing_enable(True)
+    for _ in range(n):
+        fused()
+    torch.cuda.synchronize()
+    t = ctx.timing_read()
+    ctx.timing_enable(False)
+    ctx.poll_error()
+    ctx.close()
+    k_ms = t["norm_gate"][0] / t["norm_gate"][1]
+    nbytes = 2.0 * B * L * d * 2
+    return {"workload": wl.name + " rms_norm + gate, d = %d, H_f = %d" % (d, H), "fused_kernel_ms": k_ms,
+            "fused_gbs": nbytes / (k_ms * 1e-3) / 1e9, "fused_wall_ms": fused_ms,
+            "framework_rms_norm_then_ag_gate_wall_ms": sep_ms}
+
+
 def overlap_leg(args, torch, ag, W, wl):
     """Several layers back to back: the gate of layer l+1 takes its input from before layer l's attention
     (previous-layer gating, Table 3), so it can run on a second stream (own context and workspace) beside layer
@@ -464,6 +513,8 @@ def main():
     ap.add_argument("--decode-batch", type=int, default=32)
     ap.add_argument("--project", action="store_true",
                     help="also time the K/V projection with the compaction in its epilogue (ag_project_compact_kv)")
+    ap.add_argument("--norm-gate", action="store_true",
+                    help="also time the gate fused with the RMS normalisation of its input (ag_rmsnorm_gate)")
     ap.add_argument("--decode-stack", action="store_true",
                     help="also time config 5's decode phase (one token through 32 layers, eager and from a HIP graph)")
     ap.add_argument("--stack-steps", type=int, default=32)
@@ -504,6 +555,7 @@ def main():
         cpu = cpu_baseline(wl, W)
     overlap = None if args.skip_overlap else overlap_leg(args, torch, ag, W, wl)
     proj = projection_leg(args, torch, ag, W, wl) if args.project and wl.x is not None else None
+    norm_gate = norm_gate_leg(args, torch, ag, W, wl) if args.norm_gate and wl.x is not None else None
     stack = None
     if args.decode_stack:
         log("[bench] config 5 decode phase, 32 layers ...")
@@ -521,7 +573,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": pre["config"], "kernel_ms": pre["kernel_ms"], "roofline": pre["roofline"],
         "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
-        "next_layer_gate_overlap": overlap, "decode_stack": stack, "kv_projection": proj, "machine": machine,
+        "next_layer_gate_overlap": overlap, "decode_stack": stack, "kv_projection": proj, "norm_gate": norm_gate, "machine": machine,
     }
     print(json.dumps(line))
 

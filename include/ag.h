@@ -99,7 +99,8 @@ ag_status ag_poll_error(ag_ctx *ctx, void *hip_stream);
  * launches are bracketed by records on the stream.  Up to 1024 launches per kernel id are remembered; later
  * ones are not timed.  Leave timing off while the stream is being captured into a HIP graph.  ag_timing_enable(ctx, 1) resets the counts; ag_timing_read waits for the recorded events and
  * returns the summed duration and the number of launches of one kernel id in [0, ag_timing_kernels()).
- * Ids: 0 gate (GEMM), 1 gate_finalize, 2 flag_scan, 3 compact, 4 prefill, 5 decode_partial, 6 decode_merge.
+ * Ids: 0 gate (GEMM), 1 gate_finalize, 2 flag_scan, 3 compact, 4 prefill, 5 decode_partial, 6 decode_merge,
+ * 7 mha_proj, 8 mha_attn, 9 norm_gate; ag_timing_kernel_name gives the names.
  */
 int ag_timing_kernels(void);
 const char *ag_timing_kernel_name(int kernel_id);
@@ -128,6 +129,22 @@ ag_status ag_probe_copy(ag_ctx *ctx, void *hip_stream, size_t bytes, double *gbs
 ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtype, int B, int L, int d_in,
                   const void *w_gate, const float *bias, int H_f, float tau, int n_sink, float *logits_out,
                   uint8_t *flags_out);
+
+/*
+ * The gate fused with the normalisation that produces its input (the kernel fusion Sec. 4.2.3 leaves as future
+ * work, for the linear gate of Sec. 3.4).  The paper's X (Eq. 3) is the attention block's input, which the decoder
+ * models of Sec. 4 obtain from the residual stream h by a root-mean-square normalisation with weights g:
+ *   x[b,t,c]     = (h[b,t,c] * r[b,t]) * g[c],  r = 1 / sqrt(mean_c h[b,t,c]^2 + eps)    (fp32, one rounding to bf16)
+ *   logit, flag  = as ag_gate computes them from the stored x
+ * in one pass over h: x_out is written for the projections that follow and the gate needs no second read of it.
+ * h, x_out [B, L, d_in], norm_w [d_in] and w_gate [d_in, H_f] bf16, 16-byte aligned (w_gate only for speed);
+ * x_out may be h itself (in-place normalisation).  bias fp32 [H_f]; logits_out fp32 [B, L, H_f] may be NULL;
+ * flags_out uint8 [B, H_f, L].  Built for bf16, d_in % 64 == 0, d_in <= 4096, eps > 0 (else AG_EUNSUPPORTED /
+ * AG_EINVAL).  Needs no more workspace than ag_gate on the same sizes.
+ */
+ag_status ag_rmsnorm_gate(ag_ctx *ctx, void *hip_stream, const void *h, ag_dtype dtype, int B, int L, int d_in,
+                          const void *norm_w, float eps, const void *w_gate, const float *bias, int H_f, float tau,
+                          int n_sink, void *x_out, float *logits_out, uint8_t *flags_out);
 
 /*
  * The paper's main gate (Sec. 3.3, Eq. 3): a small multi-head attention MHA' over the hidden states, then the

@@ -24,7 +24,7 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
-           "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
+           "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_rmsnorm_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
            "ag_compact_prefill_attn", "ag_project_compact_kv", "ag_project_compact_workspace_bytes", "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
 
 
@@ -81,6 +81,8 @@ def load() -> C.CDLL:
     lib.ag_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double)]
     lib.ag_gate.restype = C.c_int
     lib.ag_gate.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, f32, i32, vp, vp]
+    lib.ag_rmsnorm_gate.restype = C.c_int
+    lib.ag_rmsnorm_gate.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, f32, vp, vp, i32, f32, i32, vp, vp, vp]
     lib.ag_compact_kv.restype = C.c_int
     lib.ag_compact_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.POINTER(ag_kv_cache)]
     lib.ag_prefill_attn.restype = C.c_int
@@ -216,6 +218,17 @@ def ag_gate(ctx: Context, feat, w_gate, bias, tau: float, n_sink: int, logits_ou
     H_f = w_gate.shape[1]
     ctx._check(ctx._lib.ag_gate(ctx._h, _stream_ptr(stream), _ptr(feat), _dtype_code(feat), B, L, d_in,
                                 _ptr(w_gate), _ptr(bias), H_f, tau, n_sink, _ptr(logits_out), _ptr(flags_out)))
+
+
+def ag_rmsnorm_gate(ctx: Context, h, norm_w, eps: float, w_gate, bias, tau: float, n_sink: int, x_out, logits_out,
+                    flags_out, stream=None) -> None:
+    """h [B, L, d_in], norm_w [d_in], w_gate [d_in, H_f], bias f32 [H_f] -> x_out [B, L, d_in] (may be h),
+    logits_out f32 [B, L, H_f] (or None), flags_out u8 [B, H_f, L]."""
+    B, L, d_in = h.shape
+    H_f = w_gate.shape[1]
+    ctx._check(ctx._lib.ag_rmsnorm_gate(ctx._h, _stream_ptr(stream), _ptr(h), _dtype_code(h), B, L, d_in,
+                                        _ptr(norm_w), eps, _ptr(w_gate), _ptr(bias), H_f, tau, n_sink, _ptr(x_out),
+                                        _ptr(logits_out), _ptr(flags_out)))
 
 
 def ag_compact_kv(ctx: Context, k, v, flags, pos0: int, cache: KVCache, stream=None) -> None:

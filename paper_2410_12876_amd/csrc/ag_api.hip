@@ -119,7 +119,7 @@ void ag_destroy(ag_ctx *ctx) {
 
 static const char *const kKernelNames[AG_K_COUNT] = {"gate", "gate_finalize", "flag_scan", "compact",
                                                      "prefill", "decode_partial", "decode_merge",
-                                                     "mha_proj", "mha_attn"};
+                                                     "mha_proj", "mha_attn", "norm_gate"};
 
 int ag_timing_kernels(void) { return AG_K_COUNT; }
 
@@ -234,6 +234,37 @@ ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtyp
   hipError_t e = ag_launch_gate(ctx, (hipStream_t)hip_stream, feat, dtype, B, L, d_in, w_gate, bias, H_f, thr,
                                 n_sink, logits_out, flags_out, ws);
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_gate: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes, ws.off);
+  AG_HIP(e);
+  return AG_OK;
+}
+
+ag_status ag_rmsnorm_gate(ag_ctx *ctx, void *hip_stream, const void *h, ag_dtype dtype, int B, int L, int d_in,
+                          const void *norm_w, float eps, const void *w_gate, const float *bias, int H_f, float tau,
+                          int n_sink, void *x_out, float *logits_out, uint8_t *flags_out) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(h && norm_w && w_gate && bias && x_out && flags_out, AG_EINVAL, "ag_rmsnorm_gate: null pointer");
+  AG_REQUIRE(B > 0 && L > 0 && d_in > 0 && H_f > 0, AG_EINVAL, "ag_rmsnorm_gate: B, L, d_in, H_f must be positive");
+  AG_REQUIRE(tau > 0.f && tau < 1.f, AG_EINVAL, "ag_rmsnorm_gate: tau must lie in (0, 1)");
+  AG_REQUIRE(eps > 0.f, AG_EINVAL, "ag_rmsnorm_gate: eps must be positive");
+  AG_REQUIRE(n_sink >= 0, AG_EINVAL, "ag_rmsnorm_gate: n_sink is negative");
+  AG_REQUIRE(dtype_ok(dtype), AG_EINVAL, "ag_rmsnorm_gate: unknown dtype %d", (int)dtype);
+  AG_REQUIRE(dtype == AG_BF16, AG_EUNSUPPORTED, "ag_rmsnorm_gate: only bf16 is built");
+  AG_REQUIRE(d_in % 64 == 0 && d_in <= 4096, AG_EUNSUPPORTED,
+             "ag_rmsnorm_gate: d_in must be a multiple of 64 and at most 4096 (got %d)", d_in);
+  AG_REQUIRE(H_f <= 32, AG_EUNSUPPORTED, "ag_rmsnorm_gate: H_f = %d exceeds 32", H_f);
+  AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_rmsnorm_gate: L = %d exceeds %d", L, kMaxL);
+  AG_REQUIRE(((uintptr_t)h & 15) == 0 && ((uintptr_t)x_out & 15) == 0 && ((uintptr_t)norm_w & 15) == 0, AG_EINVAL,
+             "ag_rmsnorm_gate: h, x_out and norm_w must be 16-byte aligned");
+  AG_REQUIRE(ag_ws_gate_bytes((int64_t)B * L, d_in, H_f, dtype) <= ctx->ws_bytes, AG_EWORKSPACE,
+             "ag_rmsnorm_gate: workspace of %zu bytes is too small", ctx->ws_bytes);
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  const float thr = (float)log((double)tau / (1.0 - (double)tau));
+  ws_cursor ws = cursor(ctx);
+  hipError_t e = ag_launch_norm_gate(ctx, (hipStream_t)hip_stream, h, B, L, d_in, norm_w, eps, w_gate, bias, H_f, thr,
+                                     n_sink, x_out, logits_out, flags_out, ws);
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_rmsnorm_gate: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes,
+             ws.off);
   AG_HIP(e);
   return AG_OK;
 }

@@ -14,6 +14,8 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 #define AG_LDS __attribute__((address_space(3)))
@@ -242,6 +244,197 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
   }
 }
 
+// RMS normalisation fused with the gate: x = h / sqrt(mean_c h^2 + eps) * g, rounded once to bf16, written out for
+// the projections that follow, and multiplied by W from the same registers, so the gate costs no second read of x.
+// One workgroup of 8 waves per 32 tokens.  Wave w owns the 64-feature chunks w, w + 8, ... (at most kNormChunks of
+// them: d_in <= 4096) of all 32 rows and keeps them in registers for the whole kernel, so all loads of the tile are
+// in flight at once.  A chunk is one 128-byte line per row; a load or store instruction moves 8 whole lines (lane
+// -> row 8 i + lane / 8, 16-byte piece lane % 8).  The squares are summed per lane, over the 8 lanes of a row and
+// then over the waves through LDS in wave order.  After the scaling the chunk is stored from the same registers
+// and handed through a 4 KiB LDS buffer of the wave (pieces XOR-swizzled with the row: no bank conflicts on either
+// side) to the MFMA's A layout, lane (token m, half kb) holding features kb*32 + s*8 .. +7 for step s.  That
+// layout, the W fragments and the order of the MFMAs (chunks ascending per wave, then the waves in order) are
+// those of ag_gate_fused_kernel with one K split, so the logits are those ag_gate gives on the stored x bit for
+// bit whenever that kernel runs unsplit.
+constexpr int kNormChunks = 8;
+template <bool RAW>
+__global__ __launch_bounds__(64 * kFusedWaves, 1) void ag_norm_gate_kernel(
+    const uint16_t *h, const uint16_t *__restrict__ g, float eps, const uint4 *__restrict__ wp,
+    int64_t tokens, int d_in, int L, int H_f, const float *__restrict__ bias, float thr, int n_sink,
+    uint16_t *x_out, float *__restrict__ logits, uint8_t *__restrict__ flags) {
+  // [wave][4 KiB]: the wave's hand-over buffer (chunk of x, then chunk of W), afterwards its 32 x 32 fp32 partial tile
+  __shared__ __attribute__((aligned(16))) uint8_t wst[kFusedWaves][2][4096];
+  __shared__ __attribute__((aligned(16))) uint16_t g_l[kFusedWaves * kNormChunks * 64];
+  __shared__ float ssq_l[kFusedWaves][32];
+  __shared__ uint8_t fl[kNP][32];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: chunk offsets stay in SGPRs
+  const int m = lane & 31, kb = lane >> 5;
+  const int lr = lane >> 3, lp = lane & 7;  // row within a group of 8 and 16-byte piece of the memory-side layout
+  const int64_t tok0 = (int64_t)blockIdx.x * 32;
+  const int nchunks = d_in / 64;
+  // The tile's rows through buffer descriptors: a load or store is one per-lane offset plus a scalar chunk offset.
+  // Rows past the last token are read as the last token's row again and never stored.
+  const int rows = (int)min((int64_t)32, tokens - tok0);
+  const uint32_t tile_bytes = (uint32_t)rows * (uint32_t)d_in * 2u;
+  const __amdgpu_buffer_rsrc_t h_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(h + (size_t)tok0 * d_in), 0, tile_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(x_out + (size_t)tok0 * d_in), 0, tile_bytes, 0x00020000);
+  int row_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) row_off[i] = min(8 * i + lr, rows - 1) * d_in * 2 + lp * 16;
+  auto to_u4 = [](u32x4 v) { return make_uint4(v[0], v[1], v[2], v[3]); };
+  uint4 a[kNormChunks][4];
+#pragma unroll
+  for (int p = 0; p < kNormChunks; ++p) {
+    const int c = min(wave + kFusedWaves * p, nchunks - 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[p][i] = to_u4(__builtin_amdgcn_raw_buffer_load_b128(h_rsrc, row_off[i], c * 128, 0));
+  }
+  // W fragments (see ag_gate_fused_kernel for the two forms of wp), requested two chunks ahead of their use
+  const int chunk_u4 = 8 * H_f;
+  const __amdgpu_buffer_rsrc_t w_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void *)wp, 0, (uint32_t)d_in * (RAW ? H_f : kNP) * 2u, 0x00020000);
+  int w_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) w_off[s] = RAW ? min(s * 64 + lane, chunk_u4 - 1) * 16 : s * 1024 + lane * 16;
+  auto load_w = [&](uint4 (&bw)[4], int p) {
+    const int c = min(wave + kFusedWaves * p, nchunks - 1);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      bw[s] = to_u4(__builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_off[s], c * (RAW ? chunk_u4 * 16 : 4096), 0));
+  };
+  uint4 b[3][4];
+  load_w(b[0], 0);
+  load_w(b[1], 1);
+  // the normalisation weights: 16 bytes per thread cover 4096 of them
+  if (threadIdx.x * 8 < d_in)
+    *reinterpret_cast<uint4 *>(&g_l[threadIdx.x * 8]) = *reinterpret_cast<const uint4 *>(g + threadIdx.x * 8);
+
+  float ssq[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int p = 0; p < kNormChunks; ++p)
+    if (wave + kFusedWaves * p < nchunks) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t wd[4] = {a[p][i].x, a[p][i].y, a[p][i].z, a[p][i].w};
+        // two squares per instruction, on the packed pair as it is (v_dot2_f32_bf16, fp32 sum)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          ssq[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, wd[e]), __builtin_bit_cast(bf16x2, wd[e]), ssq[i], false);
+      }
+    }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    ssq[i] += __shfl_xor(ssq[i], 1, 64);
+    ssq[i] += __shfl_xor(ssq[i], 2, 64);
+    ssq[i] += __shfl_xor(ssq[i], 4, 64);
+    if (lp == 0) ssq_l[wave][8 * i + lr] = ssq[i];
+  }
+  __syncthreads();  // (also publishes g_l)
+  float r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) tot += ssq_l[w][8 * i + lr];
+    r[i] = 1.f / sqrtf(tot / (float)d_in + eps);
+  }
+
+  AG_LDS uint8_t *xst = (AG_LDS uint8_t *)wst[wave][0], *stage = (AG_LDS uint8_t *)wst[wave][1];
+  const int gl = lane >> 4, li = lane & 15;
+  const int tr_col = min(16 * (gl & 1) + 4 * (li & 3), H_f - 4);
+  const int tr_off = ((gl >> 1) * 32 + (li >> 2)) * (H_f * 2) + tr_col * 2;
+  auto wave_sync = [] {  // lanes of one wave exchange data through LDS
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  f32x16 acc;
+#pragma unroll
+  for (int r16 = 0; r16 < 16; ++r16) acc[r16] = 0.f;
+#pragma unroll
+  for (int p = 0; p < kNormChunks; ++p) {
+    __builtin_amdgcn_sched_barrier(0);  // one chunk at a time: interleaving them costs more registers than it hides
+    if (p + 2 < kNormChunks) load_w(b[(p + 2) % 3], p + 2);
+    const bool valid = wave + kFusedWaves * p < nchunks;  // wave-uniform
+    const int c = wave + kFusedWaves * p;
+    if (valid) {
+      const uint4 gw = *reinterpret_cast<const uint4 *>(&g_l[c * 64 + lp * 8]);
+      const uint32_t gd[4] = {gw.x, gw.y, gw.z, gw.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t hd[4] = {a[p][i].x, a[p][i].y, a[p][i].z, a[p][i].w};
+        uint32_t xd[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = (__uint_as_float(hd[e] << 16) * r[i]) * __uint_as_float(gd[e] << 16);
+          const float hi = (__uint_as_float(hd[e] & 0xffff0000u) * r[i]) * __uint_as_float(gd[e] & 0xffff0000u);
+          const f32x2 pr = {lo, hi};
+          xd[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+        }
+        const u32x4 xv = {xd[0], xd[1], xd[2], xd[3]};
+        if (8 * i + lr < rows) __builtin_amdgcn_raw_buffer_store_b128(xv, x_rsrc, row_off[i], c * 128, 0);
+        *reinterpret_cast<AG_LDS u32x4 *>(xst + (8 * i + lr) * 128 + ((lp ^ lr) << 4)) = xv;
+      }
+    }
+    uint4(&bw)[4] = b[p % 3];
+    if (RAW) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        if (s * 64 + lane < chunk_u4)
+          *reinterpret_cast<AG_LDS u32x4 *>(stage + (s * 64 + lane) * 16) = u32x4{bw[s].x, bw[s].y, bw[s].z, bw[s].w};
+    }
+    wave_sync();  // the chunk's x rows and W rows are there for every lane
+    if (RAW) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((AG_LDS bf16x4 *)(stage + tr_off + (s * 8) * (H_f * 2)));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((AG_LDS bf16x4 *)(stage + tr_off + (s * 8 + 4) * (H_f * 2)));
+        bw[s] = __builtin_bit_cast(uint4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+    }
+    if (valid) {
+      u32x4 af[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        af[s] = *reinterpret_cast<const AG_LDS u32x4 *>(xst + m * 128 + (((kb * 4 + s) ^ (m & 7)) << 4));
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[s]),
+                                                      __builtin_bit_cast(bf16x8, bw[s]), acc, 0, 0, 0);
+    }
+    wave_sync();  // both buffers have been read
+  }
+  float(*red)[32][32] = reinterpret_cast<float(*)[32][32]>(wst);
+  __syncthreads();  // (red[w] is not wave w's own buffer)
+#pragma unroll
+  for (int r16 = 0; r16 < 16; ++r16) red[wave][8 * (r16 >> 2) + 4 * kb + (r16 & 3)][m] = acc[r16];
+  __syncthreads();
+  // element e = (token row e / 32, head e % 32); thread t owns e = t and t + 512
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int e = threadIdx.x + 64 * kFusedWaves * i;
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) v += red[w][e >> 5][e & 31];
+    const int rw = e >> 5, hh = e & 31;
+    const int64_t tk = tok0 + rw;
+    if (hh < H_f && tk < tokens) {
+      const float val = v + bias[hh];
+      if (logits) logits[(size_t)tk * H_f + hh] = val;
+      fl[hh][rw] = (val > thr || (int)(tk % L) < n_sink) ? 1 : 0;
+    }
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 32 * H_f; e += 64 * kFusedWaves) {
+    const int hh = e >> 5, rw = e & 31;
+    const int64_t tk = tok0 + rw;
+    if (tk >= tokens) continue;
+    const int64_t bb = tk / L;
+    flags[((size_t)bb * H_f + hh) * L + (tk - bb * L)] = fl[hh][rw];
+  }
+}
+
 // fp32 features: plain ALU path (one thread per (token, padded head)), partial [1][tokens_pad][32].
 __global__ __launch_bounds__(256) void ag_gate_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                           int64_t tokens, int d_in, int H_f,
@@ -398,5 +591,27 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
   hipLaunchKernelGGL(ag_gate_finalize_kernel, dim3((unsigned)((tokens + kFinTok - 1) / kFinTok)), dim3(256), 0, s, partial,
                      p.splits, p.tokens_pad, tokens, L, H_f, bias, thr, n_sink, logits, flags);
   ag_tock(ctx, AG_K_GATE_FINALIZE, s);
+  return hipGetLastError();
+}
+
+hipError_t ag_launch_norm_gate(ag_ctx *ctx, hipStream_t s, const void *h, int B, int L, int d_in, const void *g,
+                               float eps, const void *w, const float *bias, int H_f, float thr, int n_sink,
+                               void *x_out, float *logits, uint8_t *flags, ws_cursor &ws) {
+  const int64_t tokens = (int64_t)B * L;
+  const bool raw_w = H_f % 4 == 0 && (reinterpret_cast<uintptr_t>(w) & 15) == 0;
+  uint16_t *wp = raw_w ? nullptr : ws.take<uint16_t>((size_t)d_in * kNP);
+  if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
+  if (!raw_w) {
+    const int n = d_in * kNP;
+    hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp);
+  }
+  const dim3 grid((unsigned)((tokens + 31) / 32)), block(64 * kFusedWaves);
+  const ag_evpair ev = ag_time_kernel(ctx, AG_K_NORM_GATE);
+  if (raw_w)
+    AG_LAUNCH(ev, ag_norm_gate_kernel<true>, grid, block, 0, s, (const uint16_t *)h, (const uint16_t *)g, eps,
+              (const uint4 *)w, tokens, d_in, L, H_f, bias, thr, n_sink, (uint16_t *)x_out, logits, flags);
+  else
+    AG_LAUNCH(ev, ag_norm_gate_kernel<false>, grid, block, 0, s, (const uint16_t *)h, (const uint16_t *)g, eps,
+              (const uint4 *)wp, tokens, d_in, L, H_f, bias, thr, n_sink, (uint16_t *)x_out, logits, flags);
   return hipGetLastError();
 }

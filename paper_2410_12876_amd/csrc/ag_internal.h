@@ -9,7 +9,7 @@
 
 // Kernels that ag_timing_* can time (ids are part of the ABI, see ag.h).
 enum { AG_K_GATE = 0, AG_K_GATE_FINALIZE, AG_K_FLAG_SCAN, AG_K_COMPACT, AG_K_PREFILL, AG_K_DECODE_PARTIAL,
-       AG_K_DECODE_MERGE, AG_K_MHA_PROJ, AG_K_MHA_ATTN, AG_K_COUNT };
+       AG_K_DECODE_MERGE, AG_K_MHA_PROJ, AG_K_MHA_ATTN, AG_K_NORM_GATE, AG_K_COUNT };
 constexpr int kTimerSlots = 1024;  // launches remembered per kernel id
 constexpr int kGateTickets = 1024; // token tiles whose K splits can be counted
 
@@ -134,6 +134,11 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
                                   const void *kc, const void *vc, const int64_t *row_off, void *out,
                                   const ag_pf_plan &plan, float *part, bool out_token_major = false,
                                   ag_evpair ev = ag_evpair{nullptr, nullptr});
+
+// RMS normalisation of h (weights g, bf16, d_in <= 4096) fused with the gate; x_out may be h itself.
+hipError_t ag_launch_norm_gate(ag_ctx *ctx, hipStream_t s, const void *h, int B, int L, int d_in, const void *g,
+                               float eps, const void *w, const float *bias, int H_f, float thr, int n_sink,
+                               void *x_out, float *logits, uint8_t *flags, ws_cursor &ws);
 
 // The paper's main gate: MHA' (projection GEMM, causal attention with hp heads of 128) in front of ag_launch_gate.
 size_t ag_ws_gate_mha_bytes(int B, int L, int d_model, int hp, int H_f);

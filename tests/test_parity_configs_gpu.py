@@ -641,6 +641,41 @@ def test_project_compact_kv_feeds_the_prefill():
     ctx.close()
 
 
+# ------------------------------------------------------------------ normalisation + gate at full size
+def test_rmsnorm_gate_full_size_llama2_7b_shape():
+    """ag_rmsnorm_gate on a whole Llama2-7B-shaped layer (4096 tokens x 4096 features, 32 heads): x within one bf16
+    spacing of the oracle's stored x and nearest-rounded up to the fp32 arithmetic; logits and flags against the
+    oracle's gate of the x the kernel stored."""
+    wl = W.config2(with_qkv=False)
+    B, L, d, H = wl.B, wl.L, wl.d_model, wl.Hkv
+    g0 = np.random.default_rng(95)
+    h = W.store(wl.x.f32 * np.exp(g0.uniform(-1, 2, size=(B, L, 1))).astype(np.float32), "bf16")
+    g = W.store(1.0 + 0.1 * g0.standard_normal(d).astype(np.float32), "bf16")
+    ctx = make_ctx(B, L, H, H, 128, ag.AG_BF16, d_in=d)
+    x = torch.empty(B, L, d, dtype=torch.bfloat16, device=DEV)
+    logits = torch.empty(B, L, H, dtype=torch.float32, device=DEV)
+    flags = torch.empty(B, H, L, dtype=torch.uint8, device=DEV)
+    ag.ag_rmsnorm_gate(ctx, dev(h), dev(g), 1e-5, dev(wl.w_gate), dev(wl.bias), wl.tau, wl.n_sink, x, logits, flags)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    ctx.close()
+    got_x = host_f32(x).astype(np.float64)
+    exact = oracle.rmsnorm(h.f32, g.f32, 1e-5)
+    stored = oracle.rmsnorm(h.f32, g.f32, 1e-5, store="bf16")
+    assert np.all(np.abs(got_x - exact) <= np.abs(exact) * (2.0 ** -8) * (1 + 2.0 ** -10) + 1e-30)
+    assert np.all(np.abs(got_x - stored) <= np.abs(stored) * 2.0 ** -7)
+    n_off = int((got_x != stored).sum())
+    assert n_off <= 1e-3 * got_x.size
+    ref_logits, ref_flags = oracle.gate(got_x.astype(np.float32), wl.w_gate.f32, wl.bias, wl.tau, wl.n_sink)
+    assert np.abs(logits.cpu().numpy() - ref_logits).max() <= 1e-4
+    near = (np.abs(ref_logits - oracle.logit_threshold(wl.tau)) < 1e-3).transpose(0, 2, 1)
+    got_f = flags.cpu().numpy()
+    assert np.array_equal(got_f[~near], ref_flags[~near])
+    print("rmsnorm+gate cfg2 shape: %d of %d stored x differ from the fp64 rounding by one spacing; %d logits within "
+          "1e-3 of the threshold, %d flags differ there" % (n_off, got_x.size, int(near.sum()),
+                                                             int((got_f != ref_flags).sum())))
+
+
 # ------------------------------------------------------------------------------------------ kernel timing
 def test_kernel_timing_counts_launches_and_leaves_results_alone():
     """With timing on, the step's kernels each report the launches made and a duration that is positive and below

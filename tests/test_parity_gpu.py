@@ -122,6 +122,85 @@ def test_gate_config2_full_size():
           (near, flags.size, diff))
 
 
+# ------------------------------------------------------------------------------- normalisation + gate
+def check_rmsnorm_gate(h, g, eps, w, bias, tau, n_sink, misalign=False, what=""):
+    """x against the fp64 definition (nearest bf16 up to the fp32 arithmetic: within 2^-8 (1 + 2^-10) of the exact
+    value, and at most one bf16 spacing from the oracle's stored x), logits and flags against the oracle's gate of
+    the x the kernel stored, in place == out of place, and the unfused ag_gate on that x agrees."""
+    B, L, d = h.f32.shape
+    H = w.f32.shape[1]
+    ctx = make_ctx(B, L, H, H, 64, ag.AG_BF16, d_in=d)
+    dh, dg, db = dev(h), dev(g), dev(bias)
+    dw = dev(w)
+    if misalign:
+        buf = torch.zeros(d * H + 4, dtype=torch.bfloat16, device=DEV)
+        buf[4:].copy_(dw.reshape(-1))
+        dw = buf[4:].view(d, H)
+    x = torch.full_like(dh, 7.0)
+    logits = torch.zeros(B, L, H, dtype=torch.float32, device=DEV)
+    flags = torch.full((B, H, L), 7, dtype=torch.uint8, device=DEV)
+    ag.ag_rmsnorm_gate(ctx, dh, dg, eps, dw, db, tau, n_sink, x, logits, flags)
+    torch.cuda.synchronize()
+    got_x = host_f32(x).astype(np.float64)
+    exact = oracle.rmsnorm(h.f32, g.f32, eps)
+    stored = oracle.rmsnorm(h.f32, g.f32, eps, store="bf16")
+    assert np.all(np.abs(got_x - exact) <= np.abs(exact) * (2.0 ** -8) * (1 + 2.0 ** -10) + 1e-30), what
+    assert np.all(np.abs(got_x - stored) <= np.abs(stored) * 2.0 ** -7), what
+    n_off = int((got_x != stored).sum())
+    assert n_off <= 1e-3 * got_x.size + 2, (what, n_off)
+    ref_logits, ref_flags = oracle.gate(got_x.astype(np.float32), w.f32, bias, tau, n_sink)
+    got_l, got_f = logits.cpu().numpy(), flags.cpu().numpy()
+    assert np.abs(got_l - ref_logits).max() <= 1e-4, what
+    near = (np.abs(ref_logits - oracle.logit_threshold(tau)) < 1e-3).transpose(0, 2, 1)
+    assert np.array_equal(got_f[~near], ref_flags[~near]) and set(np.unique(got_f)) <= {0, 1}, what
+    # in place
+    x2 = dh.clone()
+    l2, f2 = torch.zeros_like(logits), torch.zeros_like(flags)
+    ag.ag_rmsnorm_gate(ctx, x2, dg, eps, dw, db, tau, n_sink, x2, l2, f2)
+    torch.cuda.synchronize()
+    assert torch.equal(x2, x) and torch.equal(l2, logits) and torch.equal(f2, flags), what
+    # the unfused gate on the stored x
+    l3, f3 = torch.zeros_like(logits), torch.zeros_like(flags)
+    ag.ag_gate(ctx, x, dw, db, tau, n_sink, l3, f3)
+    torch.cuda.synchronize()
+    assert (l3 - logits).abs().max().item() <= 1e-4, what
+    assert np.array_equal(f3.cpu().numpy()[~near], got_f[~near]), what
+    ctx.poll_error()
+    ctx.close()
+    return n_off, bool(torch.equal(l3, logits))
+
+
+@pytest.mark.parametrize("B,L,d,H,tau,n_sink,misalign", [
+    (1, 100, 256, 4, 0.5, 0, False), (2, 77, 512, 8, 0.3, 2, False), (1, 1, 64, 32, 0.5, 0, False),
+    (1, 33, 4096, 32, 0.5, 1, False), (3, 333, 1024, 6, 0.7, 1, False), (1, 2100, 2048, 32, 0.5, 0, False),
+    (1, 64, 3072, 12, 0.5, 0, True), (2, 50, 4032, 20, 0.4, 0, False)])
+def test_rmsnorm_gate_shapes(B, L, d, H, tau, n_sink, misalign):
+    """Feature counts that fill all, some and (d = 64, 256) not even one chunk per wave, head counts that take the
+    weights as stored and pre-packed, ragged last tiles; rows of very different scale, an all-zero row and a row with
+    one huge feature among them."""
+    g0 = np.random.default_rng(21)
+    hv = g0.standard_normal((B, L, d)).astype(np.float32) * np.exp(g0.uniform(-3, 3, size=(B, L, 1))).astype(np.float32)
+    hv[0, L // 2] = 0.0
+    hv[0, L - 1, d // 3] = 3.0e4
+    h = W.store(hv, "bf16")
+    g = W.store(1.0 + 0.2 * g0.standard_normal(d).astype(np.float32), "bf16")
+    w = rand_t(22, (d, H), "bf16", 1.0 / math.sqrt(d))
+    bias = g0.standard_normal(H).astype(np.float32) * 0.2
+    check_rmsnorm_gate(h, g, 1e-5, w, bias, tau, n_sink, misalign, "B%d L%d d%d H%d" % (B, L, d, H))
+
+
+def test_rmsnorm_gate_many_tokens_equals_the_unfused_gate_bit_for_bit():
+    """With 8192 tokens or more ag_gate runs its fused kernel without K splits, whose order of additions the fused
+    normalisation + gate kernel repeats: the logits of the two are the same bits."""
+    B, L, d, H = 2, 4500, 1024, 32
+    g0 = np.random.default_rng(23)
+    h = W.store(g0.standard_normal((B, L, d)).astype(np.float32) * 2.5, "bf16")
+    g = W.store(1.0 + 0.2 * g0.standard_normal(d).astype(np.float32), "bf16")
+    w = rand_t(24, (d, H), "bf16", 1.0 / math.sqrt(d))
+    _, same_bits = check_rmsnorm_gate(h, g, 1e-6, w, np.zeros(H, np.float32), 0.5, 0, False, "many tokens")
+    assert same_bits
+
+
 # ----------------------------------------------------------------------------------------------- compaction
 def run_compact(k, v, flags, row_off, pos0, fill=None):
     B, Hkv, L, D = k.f32.shape
