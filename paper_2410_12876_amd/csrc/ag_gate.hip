@@ -108,17 +108,30 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
     float *__restrict__ partial, int32_t *__restrict__ tickets) {
   // [wave][4 KiB]: W staging of the wave while it accumulates, afterwards its 32 x 32 fp32 partial tile
   __shared__ __attribute__((aligned(16))) uint8_t wst[kFusedWaves][4096];
+  // [wave][4 KiB]: a chunk of the wave's 32 feature rows on its way from the memory-side layout to the A layout
+  __shared__ __attribute__((aligned(16))) uint8_t xstage[kFusedWaves][4096];
   __shared__ uint8_t fl[kNP][32];
   __shared__ int is_last;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: chunk offsets stay in SGPRs
   const int m = lane & 31, kb = lane >> 5;
+  const int lr = lane >> 3, lp = lane & 7;  // row within a group of 8 and 16-byte piece of the memory-side layout
   const int64_t tok0 = (int64_t)blockIdx.x * 32;
   const int nchunks = d_in / 64;
   const int splits = gridDim.y, split = blockIdx.y;
   const int c_lo = (int)((int64_t)nchunks * split / splits), c_hi = (int)((int64_t)nchunks * (split + 1) / splits);
-  int64_t tok = tok0 + m;
-  if (tok >= tokens) tok = tokens - 1;  // clamp: the row is read but its result is never written
-  const uint4 *row = reinterpret_cast<const uint4 *>(x + (size_t)tok * d_in + kb * 32);
+  // Feature rows: a chunk (64 features) is one 128-byte line per row, and a load instruction fetches 8 whole
+  // lines (lane -> row 8 i + lane / 8, 16-byte piece lane % 8) instead of 64 scattered 16-byte pieces, which the
+  // texture path would take four times as long to address.  Rows past the last token repeat the last row (read,
+  // never written).  The chunk then goes through the wave's LDS buffer (pieces XOR-swizzled with the row, so that
+  // neither side has bank conflicts) to the A layout: lane (token m, half kb), step s: features kb*32 + s*8 .. +7.
+  const int rows = (int)min((int64_t)32, tokens - tok0);
+  const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(x + (size_t)tok0 * d_in), 0, (uint32_t)rows * (uint32_t)d_in * 2u, 0x00020000);
+  int row_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) row_off[i] = min(8 * i + lr, rows - 1) * d_in * 2 + lp * 16;
+  AG_LDS uint8_t *xst = (AG_LDS uint8_t *)xstage[wave];
   // RAW: a chunk is 64 * H_f * 2 bytes = 8 * H_f uint4, lane l holds uint4 l, l + 64, ... of it
   const int chunk_u4 = 8 * H_f;
   AG_LDS uint8_t *stage = (AG_LDS uint8_t *)wst[wave];
@@ -156,7 +169,10 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
     for (int p = 0; p < PF; ++p) {
       const int c = min(c0 + kFusedWaves * p, c_hi - 1);
 #pragma unroll
-      for (int s = 0; s < 4; ++s) a[p][s] = row[c * 8 + s];
+      for (int i = 0; i < 4; ++i) {
+        const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, row_off[i], c * 128, 0);
+        a[p][i] = make_uint4(t[0], t[1], t[2], t[3]);
+      }
     }
     if (RAW) {
 #pragma unroll
@@ -179,6 +195,17 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
 #pragma unroll
     for (int p = 0; p < PF; ++p)
       if (c0 + kFusedWaves * p < c_hi) {
+        wave_sync();  // the previous chunk's fragments have been read
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          *reinterpret_cast<AG_LDS u32x4 *>(xst + (8 * i + lr) * 128 + ((lp ^ lr) << 4)) =
+              u32x4{a[p][i].x, a[p][i].y, a[p][i].z, a[p][i].w};
+        wave_sync();  // the chunk's rows are there for every lane
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const u32x4 t = *reinterpret_cast<const AG_LDS u32x4 *>(xst + m * 128 + (((kb * 4 + s) ^ (m & 7)) << 4));
+          a[p][s] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[p][s]),
