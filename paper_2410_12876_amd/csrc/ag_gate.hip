@@ -101,8 +101,8 @@ __global__ __launch_bounds__(256) void ag_gate_mfma_kernel(const uint16_t *__res
 // A operand's 16-byte feature loads.  Columns n >= H_f read whatever follows in LDS; they only reach output
 // columns that are never stored.  Otherwise wp holds the fragments prepared by ag_gate_pack_w.
 constexpr int kFusedWaves = 8;
-template <bool RAW, int PF>
-__global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fused_kernel(
+template <bool RAW, int PF, int TOK>
+__global__ __launch_bounds__(64 * kFusedWaves, PF == 2 ? 2 : 1) void ag_gate_fused_kernel(
     const uint16_t *__restrict__ x, const uint4 *__restrict__ wp, int64_t tokens, int d_in, int L, int H_f,
     const float *__restrict__ bias, float thr, int n_sink, float *__restrict__ logits, uint8_t *__restrict__ flags,
     float *__restrict__ partial, int32_t *__restrict__ tickets) {
@@ -115,8 +115,10 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: chunk offsets stay in SGPRs
   const int m = lane & 31, kb = lane >> 5;
+  const int ma = m & (TOK - 1);  // A row this lane reads: with 16-token tiles the upper half of the MFMA repeats the lower
   const int lr = lane >> 3, lp = lane & 7;  // row within a group of 8 and 16-byte piece of the memory-side layout
-  const int64_t tok0 = (int64_t)blockIdx.x * 32;
+  constexpr int NI = TOK / 8;  // load instructions per chunk: 8 rows each
+  const int64_t tok0 = (int64_t)blockIdx.x * TOK;
   const int nchunks = d_in / 64;
   const int splits = gridDim.y, split = blockIdx.y;
   const int c_lo = (int)((int64_t)nchunks * split / splits), c_hi = (int)((int64_t)nchunks * (split + 1) / splits);
@@ -125,12 +127,12 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
   // texture path would take four times as long to address.  Rows past the last token repeat the last row (read,
   // never written).  The chunk then goes through the wave's LDS buffer (pieces XOR-swizzled with the row, so that
   // neither side has bank conflicts) to the A layout: lane (token m, half kb), step s: features kb*32 + s*8 .. +7.
-  const int rows = (int)min((int64_t)32, tokens - tok0);
+  const int rows = (int)min((int64_t)TOK, tokens - tok0);
   const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void *)(x + (size_t)tok0 * d_in), 0, (uint32_t)rows * (uint32_t)d_in * 2u, 0x00020000);
-  int row_off[4];
+  int row_off[NI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) row_off[i] = min(8 * i + lr, rows - 1) * d_in * 2 + lp * 16;
+  for (int i = 0; i < NI; ++i) row_off[i] = min(8 * i + lr, rows - 1) * d_in * 2 + lp * 16;
   AG_LDS uint8_t *xst = (AG_LDS uint8_t *)xstage[wave];
   // RAW: a chunk is 64 * H_f * 2 bytes = 8 * H_f uint4, lane l holds uint4 l, l + 64, ... of it
   const int chunk_u4 = 8 * H_f;
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
     for (int p = 0; p < PF; ++p) {
       const int c = min(c0 + kFusedWaves * p, c_hi - 1);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NI; ++i) {
         const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, row_off[i], c * 128, 0);
         a[p][i] = make_uint4(t[0], t[1], t[2], t[3]);
       }
@@ -197,13 +199,13 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
       if (c0 + kFusedWaves * p < c_hi) {
         wave_sync();  // the previous chunk's fragments have been read
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < NI; ++i)
           *reinterpret_cast<AG_LDS u32x4 *>(xst + (8 * i + lr) * 128 + ((lp ^ lr) << 4)) =
               u32x4{a[p][i].x, a[p][i].y, a[p][i].z, a[p][i].w};
         wave_sync();  // the chunk's rows are there for every lane
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const u32x4 t = *reinterpret_cast<const AG_LDS u32x4 *>(xst + m * 128 + (((kb * 4 + s) ^ (m & 7)) << 4));
+          const u32x4 t = *reinterpret_cast<const AG_LDS u32x4 *>(xst + ma * 128 + (((kb * 4 + s) ^ (m & 7)) << 4));
           a[p][s] = make_uint4(t[0], t[1], t[2], t[3]);
         }
 #pragma unroll
@@ -255,7 +257,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
     const int e = threadIdx.x + 64 * kFusedWaves * i;
     const int rw = e >> 5, h = e & 31;
     const int64_t tk = tok0 + rw;
-    if (h < H_f && tk < tokens) {
+    if (h < H_f && rw < TOK && tk < tokens) {
       const float val = v[i] + bias[h];
       if (logits) logits[(size_t)tk * H_f + h] = val;
       fl[h][rw] = (val > thr || (int)(tk % L) < n_sink) ? 1 : 0;
@@ -265,7 +267,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 4 ? 1 : 2) void ag_gate_fus
   for (int e = threadIdx.x; e < 32 * H_f; e += 64 * kFusedWaves) {
     const int h = e >> 5, rw = e & 31;
     const int64_t tk = tok0 + rw;
-    if (tk >= tokens) continue;
+    if (rw >= TOK || tk >= tokens) continue;
     const int64_t b = tk / L;
     flags[((size_t)b * H_f + h) * L + (tk - b * L)] = fl[h][rw];
   }
@@ -563,15 +565,19 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
   const gate_plan p = plan_gate(tokens, d_in, dt, ctx->num_cu);
   const int64_t tiles32 = (tokens + 31) / 32;
   const bool fused = dt == AG_BF16 && tiles32 >= ctx->num_cu / 4;  // enough token tiles: one fused kernel
-  int fsplits = 1;
-  if (fused) {  // K splits until the chip is covered, each wave keeping at least 2 chunks
-    while (tiles32 * fsplits < ctx->num_cu && d_in / 64 / (fsplits * 2) >= 2 * kFusedWaves && fsplits < 8 &&
-           tiles32 <= kGateTickets)
-      fsplits *= 2;
-  }
   // the fused kernel reads W as stored when its rows can be moved and transposed in 8- and 16-byte pieces
   const bool raw_w = fused && H_f % 4 == 0 && (reinterpret_cast<uintptr_t>(w) & 15) == 0;
-  float *partial = fused ? (fsplits > 1 ? ws.take<float>((size_t)tiles32 * fsplits * 1024) : nullptr)
+  // Fewer 32-token tiles than CUs: tiles of 16 tokens first (twice the workgroups, no exchange of partial sums
+  // between them; the MFMA's upper half then idles, which costs nothing here), K splits only after that.
+  const bool tok16 = raw_w && tiles32 < ctx->num_cu;
+  const int64_t tiles = tok16 ? (tokens + 15) / 16 : tiles32;
+  int fsplits = 1;
+  if (fused) {  // K splits until the chip is covered, each wave keeping at least 2 chunks
+    while (tiles * fsplits < ctx->num_cu && d_in / 64 / (fsplits * 2) >= 2 * kFusedWaves && fsplits < 8 &&
+           tiles <= kGateTickets)
+      fsplits *= 2;
+  }
+  float *partial = fused ? (fsplits > 1 ? ws.take<float>((size_t)tiles * fsplits * 1024) : nullptr)
                          : ws.take<float>((size_t)p.splits * p.tokens_pad * kNP);
   int32_t *tickets = fused && fsplits > 1 ? ctx->gate_tickets : nullptr;
   uint16_t *wp = dt == AG_BF16 && !raw_w ? ws.take<uint16_t>((size_t)d_in * kNP) : nullptr;
@@ -582,21 +588,25 @@ hipError_t ag_launch_gate(ag_ctx *ctx, hipStream_t s, const void *feat, ag_dtype
       hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp);
     }
     if (fused) {
-      const dim3 grid((unsigned)tiles32, fsplits), block(64 * kFusedWaves);
+      const dim3 grid((unsigned)tiles, fsplits), block(64 * kFusedWaves);
       const ag_evpair ev = ag_time_kernel(ctx, AG_K_GATE);
       // PF = feature chunks a wave keeps in flight.  A launch of at most one workgroup per CU is one round of loads
       // per wave (PF = 4); a longer one runs two workgroups per CU with half the registers (PF = 2), so that one
       // loads while the other reduces and writes its flags.
-      const bool two_per_cu = (int64_t)tiles32 * fsplits > ctx->num_cu;
-#define AG_GATE_FUSED(RAWV, PFV, WPTR)                                                                             \
-  AG_LAUNCH(ev, (ag_gate_fused_kernel<RAWV, PFV>), grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)(WPTR), \
+      const bool two_per_cu = (int64_t)tiles * fsplits > ctx->num_cu;
+#define AG_GATE_FUSED(RAWV, PFV, WPTR) AG_GATE_FUSED_T(RAWV, PFV, 32, WPTR)
+#define AG_GATE_FUSED_T(RAWV, PFV, TOKV, WPTR)                                                                            \
+  AG_LAUNCH(ev, (ag_gate_fused_kernel<RAWV, PFV, TOKV>), grid, block, 0, s, (const uint16_t *)feat, (const uint4 *)(WPTR), \
                      tokens, d_in, L, H_f, bias, thr, n_sink, logits, flags, partial, tickets)
-      if (raw_w) {
+      if (tok16) {  // (16-token tiles hold half the bytes per chunk: 8 chunks in flight when a wave has that many)
+        if (d_in / 64 / fsplits > 4 * kFusedWaves) AG_GATE_FUSED_T(true, 8, 16, w); else AG_GATE_FUSED_T(true, 4, 16, w);
+      } else if (raw_w) {
         if (two_per_cu) AG_GATE_FUSED(true, 2, w); else AG_GATE_FUSED(true, 4, w);
       } else {
         AG_GATE_FUSED(false, 4, wp);  // measured: the pre-packed path is slower with two workgroups per CU
       }
 #undef AG_GATE_FUSED
+#undef AG_GATE_FUSED_T
       return hipGetLastError();
     }
     const dim3 grid(p.tiles, p.splits);
