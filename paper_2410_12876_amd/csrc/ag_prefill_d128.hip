@@ -75,6 +75,18 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
+// a * b rounded, then + c rounded: never contracted into a fused multiply-add (whose result would depend on which
+// of two chunk states plays the part of c), whatever the compiler's contraction setting
+__device__ __forceinline__ float mul_round_add(float a, float b, float c) {
+#pragma clang fp contract(off)
+  const float prod = a * b;
+  return prod + c;
+}
+__device__ __forceinline__ float mul_round(float a, float b) {
+#pragma clang fp contract(off)
+  return a * b;
+}
+
 // GB = query heads of one KV group per workgroup (one per wave).  n_split = chunks per item in the grid,
 // chunk_tiles_dev = key tiles per chunk (device value, NULL without a split); part = partial states
 // [item][chunk][4 waves][66][64] fp32 and tickets = per-item arrival counters (n_split > 1).
@@ -567,24 +579,32 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     float m = m_run;
     for (int c = 0; c < n_chunks; ++c)
       if (c != chunk) m = fmaxf(m, peek(&st[c * cstride + 64 * 64]));
-    const float f_own = __builtin_amdgcn_exp2f(m_run - m);
-    l_run = __fmul_rn(l_run, f_own);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc_o[dt][r] = __fmul_rn(acc_o[dt][r], f_own);
-    for (int c = 0; c < n_chunks; ++c) {
-      if (c == chunk) continue;
-      const float *sc = st + c * cstride;
-      const float f = __builtin_amdgcn_exp2f(peek(&sc[64 * 64]) - m);
-      // rounded product + rounded product (no fused multiply-add): the sum of two chunks is then the same
-      // bit pattern whichever of them arrives last and does the merge
-      l_run = __fadd_rn(__fmul_rn(peek(&sc[65 * 64]), f), l_run);
+    // Rounded product + rounded product (never a fused multiply-add), so that the result does not depend on which chunk
+    // arrives last: two chunks are one commutative addition of this chunk's registers and the other's state; more
+    // are added in chunk order starting from zero, this chunk's own state read back like the others'.
+    if (n_chunks == 2) {
+      const float f_own = __builtin_amdgcn_exp2f(m_run - m);
+      l_run = mul_round(l_run, f_own);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          acc_o[dt][r] = __fadd_rn(__fmul_rn(peek(&sc[(16 * dt + r) * 64]), f), acc_o[dt][r]);
+        for (int r = 0; r < 16; ++r) acc_o[dt][r] = mul_round(acc_o[dt][r], f_own);
+    } else {
+      l_run = 0.f;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.f;
+    }
+    for (int c = 0; c < n_chunks; ++c) {
+      if (n_chunks == 2 && c == chunk) continue;
+      const float *sc = st + c * cstride;
+      const float f = __builtin_amdgcn_exp2f(peek(&sc[64 * 64]) - m);
+      l_run = mul_round_add(peek(&sc[65 * 64]), f, l_run);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[dt][r] = mul_round_add(peek(&sc[(16 * dt + r) * 64]), f, acc_o[dt][r]);
     }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -620,9 +640,15 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
   plan->max_tiles = (L + kBN - 1) / kBN;
   plan->slots = (8 / plan->NW) * num_cu;
   plan->n_split = 1;
-  // (at most two chunks: the merge adds two rounded products, which is the same bit pattern in either order; more
-  // chunks would need a fixed merge order to stay reproducible)
-  if (items < (int64_t)8 * num_cu && plan->max_tiles > 16) plan->n_split = 2;
+  // Two chunks at most per item, unless the items are so few (few heads) that even their halves leave workgroup
+  // slots empty: then more, until the chunks cover the slots (the merge adds the states in chunk order, so it stays
+  // reproducible).  Measured with 4 heads x 4096 all-kept tokens: 2 chunks 54 us, up to 4 chunks 49.5 us, up to 8
+  // chunks 68 us -- the chunk that arrives last fetches the other states one after the other.
+  if (items < (int64_t)8 * num_cu && plan->max_tiles > 16) {
+    plan->n_split = 2;
+    while (items * plan->n_split < (int64_t)plan->slots && plan->n_split < 8 && plan->max_tiles / (2 * plan->n_split) >= 8)
+      plan->n_split *= 2;
+  }
   *part = nullptr;
   if (plan->n_split > 1) {
     *part = ws.take<float>((size_t)items * plan->n_split * plan->NW * 66 * 64);

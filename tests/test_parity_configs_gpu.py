@@ -169,7 +169,8 @@ def _prefill_case(B, Hq, Hkv, L, flags, seed, with_cache=True):
 
 @pytest.mark.parametrize("name,B,Hq,Hkv,L", [
     ("split in two key chunks, balanced order", 1, 16, 16, 2048),
-    ("split, heads not a multiple of 8 (no reordering)", 1, 3, 3, 4096),
+    ("few heads: up to 8 key chunks per item, heads not a multiple of 8 (no reordering)", 1, 3, 3, 4096),
+    ("few heads, GQA, long prompt: 4 key chunks", 1, 8, 2, 8192),
     ("large launch, no split", 4, 32, 32, 2048),
     ("more than 1024 units (plan off)", 36, 32, 32, 256),
     ("GQA split", 1, 32, 8, 2048),
@@ -202,6 +203,10 @@ def test_prefill_and_gate_are_reproducible_bit_for_bit():
     assert torch.equal(a, b)
     c = _prefill_case(B, H, H, L, flags, 81, with_cache=False)[3]      # internal compaction: same rows, same result
     assert torch.equal(a, c)
+    # few heads: items are cut into up to 8 key chunks, whose states are added in chunk order whoever arrives last
+    flags4 = (g.random((1, 4, L)) < np.array([1.0, 0.9, 0.5, 0.2])[None, :, None]).astype(np.uint8)
+    runs = [_prefill_case(1, 4, 4, L, flags4, 82)[3] for _ in range(3)]
+    assert torch.equal(runs[0], runs[1]) and torch.equal(runs[0], runs[2])
     x = W.store(g.standard_normal((B, L, 4096)).astype(np.float32) * 0.5, "bf16")
     w = W.store(g.standard_normal((4096, H)).astype(np.float32) / 64.0, "bf16")
     bias = np.zeros(H, np.float32)
@@ -215,6 +220,45 @@ def test_prefill_and_gate_are_reproducible_bit_for_bit():
         ctx.close()
         res.append((lo, fo))
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+
+
+def test_prefill_split_merge_is_reproducible_whichever_chunk_arrives_last():
+    """Items cut into key chunks are merged by the chunk that arrives last, and which one that is changes with the
+    load on the chip.  Two problems alternate on one context (so a state left over from the previous launch would be
+    another problem's), half of the launches beside a stream of HBM traffic: every result must be the bits of the
+    problem's first run.  (A product contracted into a fused multiply-add made the sum depend on the arrival order
+    by one fp32 rounding; this is the regression test.)"""
+    B, H, L, D = 1, 16, 2048, 128
+    g = np.random.default_rng(83)
+    sets = []
+    for s in range(2):
+        q, k, v = (dev(W.store(g.standard_normal((B, H, L, D)).astype(np.float32) * (1.0 + s), "bf16")) for _ in range(3))
+        keep = np.linspace(0.95, 0.3, H)[None, :, None]
+        sets.append((q, k, v, dev((g.random((B, H, L)) < keep).astype(np.uint8))))
+    ro = oracle.slab_row_off(B * H, L)
+    ctx = make_ctx(B, L, H, H, D, ag.AG_BF16)
+    side = torch.cuda.Stream()
+    junk = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)
+
+    def run(s, load):
+        q, k, v, flags = sets[s]
+        cache = new_cache(B, H, D, torch.bfloat16, ro)
+        out = torch.empty_like(q)
+        if load:
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for _ in range(4):
+                    junk.add_(1)
+        ag.ag_compact_prefill_attn(ctx, q, k, v, flags, 1.0 / math.sqrt(D), 0, cache, out)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        return out
+
+    base = [run(0, False), run(1, False)]
+    for it in range(80):
+        assert torch.equal(run(it % 2, it % 4 >= 2), base[it % 2]), it
+    ctx.poll_error()
+    ctx.close()
 
 
 # ------------------------------------------------------------------------------------------------ HIP graph
