@@ -196,7 +196,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   // steps of this workgroup: the band tiles first, then its chunk of compacted tiles
   const int n_steps = n_band + max(0, min(n_tiles - tile0, chunk_tiles));
 
-  const size_t qrow = ((size_t)(b * Hq + head) * L + jq) * D;
   const size_t kvrow = ((size_t)u * L + jq) * D;
   const uint16_t *Kc = kc + (size_t)ro0 * D;
   const uint16_t *Vc = vc + (size_t)ro0 * D;
@@ -608,18 +607,39 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (j0 + col < L) {
-    const float inv = 1.f / l_tot;
-    // head-major [B, Hq, L, D] like q, or token-major [B, L, Hq, D] (heads of a token side by side)
-    uint16_t *orow = out + (out_token_major ? (((size_t)b * L + jq) * Hq + head) * D : qrow);
+  const float inv = 1.f / l_tot;
+  // Output rows leave as whole 256-byte rows.  A lane owns one query and 4-element pieces of its row, so direct
+  // stores would be 16 instructions of 64 scattered 8-byte pieces each; instead the wave lays its 32 rows out in
+  // 8 KiB of the (now unused) tile buffers, 16-byte chunks XOR-swizzled with the row, and stores them with 8
+  // instructions of 4 whole rows each (lane -> row 4 i + lane / 16, chunk lane % 16).
+  __syncthreads();  // every wave is done with the K/V tiles
+  {
+    AG_LDS uint8_t *ost = (AG_LDS uint8_t *)smem + w4 * (32 * kRowB);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const uint2 o = make_uint2(pack2(acc_o[dt][4 * r4 + 0] * inv, acc_o[dt][4 * r4 + 1] * inv),
-                                   pack2(acc_o[dt][4 * r4 + 2] * inv, acc_o[dt][4 * r4 + 3] * inv));
-        *reinterpret_cast<uint2 *>(orow + 32 * dt + 8 * r4 + 4 * hb) = o;
+        const u32x2 o = {pack2(acc_o[dt][4 * r4 + 0] * inv, acc_o[dt][4 * r4 + 1] * inv),
+                         pack2(acc_o[dt][4 * r4 + 2] * inv, acc_o[dt][4 * r4 + 3] * inv)};
+        *reinterpret_cast<AG_LDS u32x2 *>(ost + col * kRowB + (((4 * dt + r4) ^ (col & 15)) << 4) + 8 * hb) = o;
       }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // one lane's store is another lane's load
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // head-major [B, Hq, L, D] like q, or token-major [B, L, Hq, D] (heads of a token side by side): the wave's rows
+    // start at a wave-uniform address and lie row_stride apart
+    const int row_stride = (out_token_major ? Hq : 1) * kRowB;
+    uint16_t *obase = out + (out_token_major ? (((size_t)b * L + j0) * Hq + head) * D : ((size_t)(b * Hq + head) * L + j0) * D);
+    const int n_rows = min(32, L - j0);  // <= 0 for a wave past the end of the prompt: nothing is stored
+    const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)obase, 0, n_rows > 0 ? (uint32_t)((n_rows - 1) * row_stride + kRowB) : 0u, 0x00020000);
+    const int orow_l = lane >> 4, ochunk = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = 4 * i + orow_l;
+      const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(ost + row * kRowB + ((ochunk ^ (row & 15)) << 4));
+      if (row < n_rows) __builtin_amdgcn_raw_buffer_store_b128(x, o_rsrc, orow_l * row_stride + ochunk * 16, i * 4 * row_stride, 0);
+    }
   }
 }
 
