@@ -101,6 +101,7 @@ struct ag_pf_plan {
   int n_hy, HB, BM, n_items, n_split, slots, max_tiles;
   int NW;                // waves per workgroup of the prefill kernel (4 or 8)
   int head_major;        // block order of the prefill kernel: a head's query tiles together (many heads)
+  int n_sp;              // query-tile rows (the longest ones) that can hold an item longer than one chunk
 };
 
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----

@@ -31,6 +31,8 @@
 //     to the next, so every engine gets about the same number of key tiles although heads keep 20 % to 90 %.
 #include <string.h>
 
+#include <algorithm>
+
 #include "ag_internal.h"
 
 #ifdef AG_PREFILL_TRACE  // debug build only: per-workgroup start/end times and placement
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw, int n_hy,
-    int n_split, const int32_t *__restrict__ chunk_tiles_dev, float qscale, int n_recent,
+    int n_split, int n_sp, const int32_t *__restrict__ chunk_tiles_dev, float qscale, int n_recent,
     const int32_t *__restrict__ order, int head_major, uint16_t *__restrict__ out, int out_token_major,
     float *__restrict__ part, int32_t *__restrict__ tickets) {
   constexpr int QW = NW / GB;  // query sub-tiles per workgroup
@@ -120,10 +122,22 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   const int col = lane & 31, hb = lane >> 5;
   // workgroup id -> (query tile, chunk, unit/head block): heads vary fastest so that a head keeps its XCD
   const int n_qt = (L + BM - 1) / BM;
+  // The first n_sp rows of query tiles (the longest) have n_split workgroups per item, one per key chunk; a shorter
+  // row cannot hold an item of more than one chunk (a chunk is never shorter than max_tiles / n_split tiles) and has
+  // one workgroup per item.
   const int per_qt = n_hy * n_split;
-  int rem = blockIdx.x % per_qt;
-  const int chunk = rem / n_hy;
-  int qt_idx = blockIdx.x / per_qt;
+  const int split_blocks = n_sp * per_qt;
+  int rem, chunk, qt_idx;
+  if ((int)blockIdx.x < split_blocks) {
+    rem = blockIdx.x % per_qt;
+    chunk = rem / n_hy;
+    qt_idx = blockIdx.x / per_qt;
+  } else {
+    const int r2 = blockIdx.x - split_blocks;
+    rem = r2 % n_hy;
+    chunk = 0;
+    qt_idx = n_sp + r2 / n_hy;
+  }
   if (head_major) {
     // Many heads: the resident workgroups should cover few of them, or a head's K/V rows leave the L2 between
     // two of its query tiles and every tile comes from HBM again.  XCD x (workgroups x, x + 8, ...) walks heads
@@ -675,6 +689,15 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
     plan->chunk_tiles = ws.take<int32_t>(64);
     plan->tickets = ws.take<int32_t>((size_t)items);
   }
+  // rows of query tiles whose items can exceed one chunk: (t + 1) BM tokens give at most that many / 64 key tiles
+  const int n_qt_all = (L + plan->BM - 1) / plan->BM;
+  plan->n_sp = n_qt_all;
+  if (plan->n_split > 1) {
+    const int lo = (plan->max_tiles + plan->n_split - 1) / plan->n_split;
+    int shorter = 0;  // rows t = 0 .. shorter - 1 never exceed lo tiles
+    while (shorter < n_qt_all && (std::min((shorter + 1) * plan->BM, L) + kBN - 1) / kBN <= lo) ++shorter;
+    plan->n_sp = n_qt_all - shorter;
+  }
   // 16 or more heads per XCD: head-major block order (K/V reuse in the L2); fewer: a head order balanced by kept rows
   plan->head_major = plan->n_split == 1 && plan->n_hy >= 128;
   if (!plan->head_major && plan->n_hy % 8 == 0 && plan->n_hy >= 16 && plan->n_hy <= 256)
@@ -699,13 +722,14 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
   const int GB = G >= 4 ? 4 : G;
   if ((int64_t)plan.n_items * plan.n_split > 0x7fffffff) return hipErrorInvalidValue;
   const int n_qt = plan.n_items / plan.n_hy;
-  const int64_t blocks = plan.head_major ? (int64_t)((plan.n_hy + 7) / 8) * 8 * n_qt : (int64_t)plan.n_items * plan.n_split;
+  const int64_t blocks = plan.head_major ? (int64_t)((plan.n_hy + 7) / 8) * 8 * n_qt
+                                         : (int64_t)plan.n_hy * (plan.n_sp * plan.n_split + (n_qt - plan.n_sp));
   const dim3 grid((unsigned)blocks), block(64 * plan.NW);
 #define AG_PF(GG, BB) AG_PFN(GG, BB, 4)
 #define AG_PFN(GG, BB, NN)                                                                                          \
   AG_LAUNCH(ev, (ag_prefill_d128_kernel<GG, BB, NN>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k, \
                      (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
-                     Hkv, nw, plan.n_hy, plan.n_split, plan.chunk_tiles, qscale, n_recent, plan.order,               \
+                     Hkv, nw, plan.n_hy, plan.n_split, plan.n_sp, plan.chunk_tiles, qscale, n_recent, plan.order,               \
                      plan.head_major, (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)
   if (n_recent > 1) {
     if (GB == 1) { AG_PF(1, true); } else if (GB == 2) { AG_PF(2, true); } else { AG_PF(4, true); }
