@@ -261,6 +261,73 @@ def test_prefill_split_merge_is_reproducible_whichever_chunk_arrives_last():
     ctx.close()
 
 
+def test_gate_and_decode_are_reproducible_beside_other_traffic():
+    """The gate's K splits across workgroups and the decode step's partial states are combined in a fixed order; two
+    problems alternate on one context, half of the calls beside a stream of HBM traffic, and every result must be the
+    bits of the problem's first run."""
+    side = torch.cuda.Stream()
+    junk = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)
+
+    def loaded(fn, load):
+        if load:
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for _ in range(4):
+                    junk.add_(1)
+        r = fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        return r
+
+    def alternate(fns, n):
+        base = [loaded(f, False) for f in fns]
+        for it in range(n):
+            got = loaded(fns[it % 2], it % 4 >= 2)
+            assert all(torch.equal(a, b) for a, b in zip(got, base[it % 2])), it
+
+    g = np.random.default_rng(84)
+    B, L, d, H = 1, 2100, 2048, 32                         # 16-token tiles and 2 K splits across workgroups
+    ctx = make_ctx(B, L, H, H, 128, ag.AG_BF16, d_in=d)
+    xs = [dev(W.store(g.standard_normal((B, L, d)).astype(np.float32) * (0.5 + s), "bf16")) for s in range(2)]
+    ws = [dev(W.store(g.standard_normal((d, H)).astype(np.float32) / math.sqrt(d), "bf16")) for s in range(2)]
+    bias = dev(np.zeros(H, np.float32))
+
+    def gate(s):
+        def f():
+            lo = torch.empty(B, L, H, dtype=torch.float32, device=DEV)
+            fl = torch.empty(B, H, L, dtype=torch.uint8, device=DEV)
+            ag.ag_gate(ctx, xs[s], ws[s], bias, 0.5, 0, lo, fl)
+            return lo, fl
+        return f
+    alternate([gate(0), gate(1)], 40)
+    ctx.close()
+
+    B, Hq, Hkv, D, cap = 8, 32, 8, 128, 4200
+    ctx = make_ctx(B, 4096, Hq, Hkv, D, ag.AG_BF16, cache_rows=B * Hkv * cap)
+    ro = oracle.slab_row_off(B * Hkv, cap)
+    sets = []
+    for s in range(2):
+        lens = g.integers(1, 4000, size=B * Hkv).astype(np.int32)
+        kc = torch.randn(B * Hkv * cap, D, device=DEV).to(torch.bfloat16) * (1 + s)
+        q = torch.randn(B, Hq, D, device=DEV).to(torch.bfloat16)
+        kn = torch.randn(B, Hkv, D, device=DEV).to(torch.bfloat16)
+        sets.append((lens, kc, torch.randn_like(kc), q, kn, torch.randn_like(kn)))
+
+    def decode(s):
+        lens, kc, vc, q, kn, vn = sets[s]
+
+        def f():
+            cache = ag.KVCache(kc.clone(), vc.clone(), torch.zeros(B * Hkv * cap, dtype=torch.int32, device=DEV),
+                               torch.from_numpy(ro).to(DEV), torch.from_numpy(lens).to(DEV), B, Hkv, D)
+            out = torch.empty_like(q)
+            ag.ag_decode_attn(ctx, q, kn, vn, None, 4096, 1.0 / math.sqrt(D), cache, out)
+            return out, cache.len
+        return f
+    alternate([decode(0), decode(1)], 40)
+    ctx.poll_error()
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------------------ HIP graph
 def test_whole_step_replays_from_a_hip_graph():
     """gate -> compaction -> prefill -> decode captured once in a HIP graph: several replays, with eager work of
