@@ -16,7 +16,7 @@ kernel on the launch stream (ag_timing_* of the C ABI) over the same number of s
   machine       : what this machine sustains (MFMA loop, streaming copy, vendor bf16 GEMM) beside the data-sheet peaks.
 Optional legs: --config 4 / --config 5 --layer l (the other layer workloads), --keep, --seq-len, --decode-stack
 (config 5's decode phase: one token through 32 layers, eager and from a HIP graph), --project (the K/V projection
-with the compaction in its epilogue), --norm-gate (the gate fused with the normalisation of its input),
+with the compaction in its epilogue), --norm-gate (the gate fused with the normalisation of its input), --power (package power under the prefill kernel),
 next_layer_gate_overlap (the next layer's gate on a second stream).
 """
 import argparse
@@ -335,6 +335,68 @@ def projection_leg(args, torch, ag, W, wl):
             "tflops": flops / (proj_ms * 1e-3) / 1e12, "separate_compaction_ms": t["compact"][0] / t["compact"][1]}
 
 
+def power_leg(args, torch, ag, W, wl):
+    """Package power while the prefill kernel of the workload runs back to back for about two seconds: the board's
+    own sensor (hwmon power1_input, microwatts) sampled from a host thread, beside its cap (power1_cap) and the idle
+    reading before the loop.  Shows whether the kernel runs into the power limit rather than an issue limit."""
+    import glob
+    import threading
+    hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*"))
+
+    def read(name):
+        for h in hw:
+            try:
+                return float(open(os.path.join(h, name)).read())
+            except (OSError, ValueError):
+                continue
+        return None
+
+    if read("power1_input") is None and read("power1_average") is None:
+        return {"available": False}
+    sensor = "power1_input" if read("power1_input") is not None else "power1_average"
+    B, L, Hq, Hkv, D = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D
+    U, cap = B * Hkv, L
+    q, k, v = to_dev(wl.q, torch), to_dev(wl.k, torch), to_dev(wl.v, torch)
+    flags = torch.from_numpy(wl.flags).cuda() if wl.flags is not None else (torch.rand(B, Hkv, L, device="cuda") < 0.55).to(torch.uint8)
+    ctx = ag.Context(0, ag.workspace_bytes(B, L, Hq, Hkv, D, ag.AG_BF16, 0, 0))
+    cache = ag.KVCache(torch.zeros(U * cap, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(U * cap, D, dtype=torch.bfloat16, device="cuda"),
+                       torch.zeros(U * cap, dtype=torch.int32, device="cuda"),
+                       torch.arange(U + 1, dtype=torch.int64, device="cuda") * cap,
+                       torch.zeros(U, dtype=torch.int32, device="cuda"), B, Hkv, D)
+    out = torch.empty_like(q)
+    ag.ag_compact_kv(ctx, k, v, flags, 0, cache)
+    ag.ag_prefill_attn(ctx, q, k, v, flags, wl.scale, cache, out)
+    torch.cuda.synchronize()
+    time.sleep(0.5)
+    idle = read(sensor)
+    samples, stop = [], [False]
+
+    def sampler():
+        while not stop[0]:
+            samples.append(read(sensor))
+            time.sleep(0.02)
+
+    th = threading.Thread(target=sampler)
+    t0 = time.perf_counter()
+    th.start()
+    n = 0
+    while time.perf_counter() - t0 < 2.0:
+        for _ in range(200):
+            ag.ag_prefill_attn(ctx, q, k, v, flags, wl.scale, cache, out)
+        torch.cuda.synchronize()
+        n += 200
+    t1 = time.perf_counter()
+    stop[0] = True
+    th.join()
+    ctx.close()
+    body = [x for x in samples[len(samples) // 4:] if x is not None]      # skip the ramp at the start
+    pcap = read("power1_cap")
+    return {"available": True, "sensor": sensor, "workload": wl.name, "prefill_us_per_launch": (t1 - t0) / n * 1e6,
+            "idle_w": idle / 1e6 if idle else None, "mean_w": sum(body) / len(body) / 1e6 if body else None,
+            "max_w": max(body) / 1e6 if body else None, "cap_w": pcap / 1e6 if pcap else None}
+
+
 def norm_gate_leg(args, torch, ag, W, wl):
     """The gate fused with the RMS normalisation that produces its input (ag_rmsnorm_gate) on the headline shape,
     beside the two separate passes it replaces: the framework's own rms_norm kernel, then ag_gate.  The residual
@@ -515,6 +577,8 @@ def main():
                     help="also time the K/V projection with the compaction in its epilogue (ag_project_compact_kv)")
     ap.add_argument("--norm-gate", action="store_true",
                     help="also time the gate fused with the RMS normalisation of its input (ag_rmsnorm_gate)")
+    ap.add_argument("--power", action="store_true",
+                    help="also sample the package power sensor while the prefill kernel runs back to back")
     ap.add_argument("--decode-stack", action="store_true",
                     help="also time config 5's decode phase (one token through 32 layers, eager and from a HIP graph)")
     ap.add_argument("--stack-steps", type=int, default=32)
@@ -556,6 +620,7 @@ def main():
     overlap = None if args.skip_overlap else overlap_leg(args, torch, ag, W, wl)
     proj = projection_leg(args, torch, ag, W, wl) if args.project and wl.x is not None else None
     norm_gate = norm_gate_leg(args, torch, ag, W, wl) if args.norm_gate and wl.x is not None else None
+    power = power_leg(args, torch, ag, W, wl) if args.power else None
     stack = None
     if args.decode_stack:
         log("[bench] config 5 decode phase, 32 layers ...")
@@ -573,7 +638,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": pre["config"], "kernel_ms": pre["kernel_ms"], "roofline": pre["roofline"],
         "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
-        "next_layer_gate_overlap": overlap, "decode_stack": stack, "kv_projection": proj, "norm_gate": norm_gate, "machine": machine,
+        "next_layer_gate_overlap": overlap, "decode_stack": stack, "kv_projection": proj, "norm_gate": norm_gate, "prefill_power": power, "machine": machine,
     }
     print(json.dumps(line))
 
