@@ -357,8 +357,13 @@ def power_leg(args, torch, ag, W, wl):
     B, L, Hq, Hkv, D = wl.B, wl.L, wl.Hq, wl.Hkv, wl.D
     U, cap = B * Hkv, L
     q, k, v = to_dev(wl.q, torch), to_dev(wl.k, torch), to_dev(wl.v, torch)
-    flags = torch.from_numpy(wl.flags).cuda() if wl.flags is not None else (torch.rand(B, Hkv, L, device="cuda") < 0.55).to(torch.uint8)
-    ctx = ag.Context(0, ag.workspace_bytes(B, L, Hq, Hkv, D, ag.AG_BF16, 0, 0))
+    ctx = ag.Context(0, ag.workspace_bytes(B, L, Hq, Hkv, D, ag.AG_BF16, wl.d_model, 0))
+    if wl.flags is not None:
+        flags = torch.from_numpy(wl.flags).cuda()
+    else:  # the workload's own flags, from its gate
+        flags = torch.empty(B, Hkv, L, dtype=torch.uint8, device="cuda")
+        ag.ag_gate(ctx, to_dev(wl.x, torch), to_dev(wl.w_gate, torch), torch.from_numpy(wl.bias).cuda(), wl.tau, wl.n_sink,
+                   None, flags)
     cache = ag.KVCache(torch.zeros(U * cap, D, dtype=torch.bfloat16, device="cuda"),
                        torch.zeros(U * cap, D, dtype=torch.bfloat16, device="cuda"),
                        torch.zeros(U * cap, dtype=torch.int32, device="cuda"),
