@@ -20,6 +20,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 #define AG_LDS __attribute__((address_space(3)))
 
 constexpr int kDh = 128;           // d'_k
@@ -170,41 +172,52 @@ __global__ __launch_bounds__(256, 2) void ag_proj_gemm_kernel(const uint16_t *__
   }
 
   // ---- epilogue: acc[nt][mt][r] = C[token m0 + 64 wm + 32 mt + col][n0 + 64 wn + 32 nt + 8 (r/4) + 4 kb + r%4] ----
+  // The tile is one head of one projection: 128 tokens x 128 features = 128 whole output rows of 256 bytes.  A lane
+  // owns 4-feature pieces of two tokens, so it would store scattered 8-byte pieces; the tile is laid out in the
+  // (now unused) operand buffers instead, 16-byte chunks XOR-swizzled with the row, and leaves as whole rows, 4 per
+  // instruction (lane -> row 4 i + lane / 16, chunk lane % 16), to the output and, for a kept token, to its cache row.
   const int hd = hp * kDh;
-  const int which_t = n0 / hd, head_t = (n0 - which_t * hd) / kDh;  // the tile is one head of one projection
+  const int which_t = n0 / hd, head_t = (n0 - which_t * hd) / kDh;
+  __syncthreads();  // every wave is done with the last k-tile
+  AG_LDS uint8_t *ost = (AG_LDS uint8_t *)smem;
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
-    const int64_t m = m0 + 64 * wm + 32 * mt + col;
+    const int row = 64 * wm + 32 * mt + col;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x16 &c = acc[nt][mt];
+        const u32x2 val = {pack2(c[4 * r4 + 0], c[4 * r4 + 1]), pack2(c[4 * r4 + 2], c[4 * r4 + 3])};
+        *reinterpret_cast<AG_LDS u32x2 *>(ost + row * 256 + (((8 * wn + 4 * nt + r4) ^ (row & 15)) << 4) + 8 * kb) = val;
+      }
+  }
+  __syncthreads();  // a row's two halves come from two waves
+  const int ochunk = lane & 15;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = 32 * wave + 4 * i + (lane >> 4);
+    const int64_t m = m0 + row;
+    const u32x4 val = *reinterpret_cast<const AG_LDS u32x4 *>(ost + row * 256 + ((ochunk ^ (row & 15)) << 4));
     if (m >= M) continue;
     const int64_t b = m / L, tt = m - b * L;
-    uint16_t *crow = nullptr;  // COMPACT: this token's row in the cache, if it is kept and fits
-    if (COMPACT) {
+    uint16_t *dst = out + (((size_t)which_t * (M / L) * hp + (size_t)b * hp + head_t) * L + tt) * kDh + 8 * ochunk;
+    *reinterpret_cast<u32x4 *>(dst) = val;
+    if (COMPACT) {  // this token's row in the cache, if it is kept and fits
       const int u = (int)b * hp + head_t;
       const uint64_t word = cp.words[(size_t)u * cp.nw + (tt >> 6)];
       if ((word >> (tt & 63)) & 1ull) {
         const int c = cp.blk_off[(size_t)u * (cp.nw + 1) + (tt >> 6)] + __popcll(word & ((1ull << (tt & 63)) - 1ull));
         const int64_t r0 = cp.row_off[u], cap = cp.row_off[u + 1] - r0;
         if (c < cap) {
-          crow = (which_t == 0 ? cp.kc : cp.vc) + (size_t)(r0 + c) * kDh;
-          if (which_t == 0 && wn == 0 && kb == 0) cp.idx[r0 + c] = cp.pos0 + (int)tt;
-        } else if (which_t == 0 && wn == 0 && kb == 0) {
+          uint16_t *crow = (which_t == 0 ? cp.kc : cp.vc) + (size_t)(r0 + c) * kDh;
+          *reinterpret_cast<u32x4 *>(crow + 8 * ochunk) = val;
+          if (which_t == 0 && ochunk == 0) cp.idx[r0 + c] = cp.pos0 + (int)tt;
+        } else if (which_t == 0 && ochunk == 0) {
           atomicOr(cp.d_err, 1);  // the row is dropped, nothing is written out of bounds
         }
       }
     }
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int n = n0 + 64 * wn + 32 * nt + 8 * r4 + 4 * kb;  // first of 4 consecutive columns (same head)
-        const int which = n / hd, rem = n - which * hd;
-        const int head = rem / kDh, dd = rem - head * kDh;
-        uint16_t *dst = out + (((size_t)which * (M / L) * hp + (size_t)b * hp + head) * L + tt) * kDh + dd;
-        const f32x16 &c = acc[nt][mt];
-        const uint2 val = make_uint2(pack2(c[4 * r4 + 0], c[4 * r4 + 1]), pack2(c[4 * r4 + 2], c[4 * r4 + 3]));
-        *reinterpret_cast<uint2 *>(dst) = val;
-        if (COMPACT && crow) *reinterpret_cast<uint2 *>(crow + dd) = val;
-      }
   }
   if (COMPACT && which_t == 0) {  // the K tile that holds a sequence's first token writes the unit's length
     const int64_t bb = (m0 + L - 1) / L + tid;  // thread t: the t-th sequence that starts inside this tile
