@@ -338,7 +338,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, TOK == 16 ? 2 : 1) void ag_norm_g
   load_w(b[0], 0);
   load_w(b[1], 1);
   // the normalisation weights: 16 bytes per thread cover 4096 of them
-  if (threadIdx.x * 8 < d_in)
+  if ((int)threadIdx.x * 8 < d_in)
     *reinterpret_cast<uint4 *>(&g_l[threadIdx.x * 8]) = *reinterpret_cast<const uint4 *>(g + threadIdx.x * 8);
 
   float ssq[NI];

@@ -210,7 +210,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   // steps of this workgroup: the band tiles first, then its chunk of compacted tiles
   const int n_steps = n_band + max(0, min(n_tiles - tile0, chunk_tiles));
 
-  const size_t kvrow = ((size_t)u * L + jq) * D;
   const uint16_t *Kc = kc + (size_t)ro0 * D;
   const uint16_t *Vc = vc + (size_t)ro0 * D;
 
