@@ -91,6 +91,8 @@ __device__ __forceinline__ void plan_tail(const ag_pf_plan &plan, int num_units,
 
 // grid = (segments, units).  A workgroup builds the mask words of its 1024 tokens and needs the number of
 // kept tokens before them; it counts those itself (4 flags per load), so no workgroup waits for another.
+// flags == nullptr stands for "every token kept" (the attention inside the gate module evicts nothing): the words
+// and counts are then written without reading anything.
 __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_t *__restrict__ flags, int L, int nw,
                                                                     uint64_t *__restrict__ words,
                                                                     int32_t *__restrict__ blk_off, ag_pf_plan plan,
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_
   __shared__ int32_t part[kScanThreads / 64];
   const int u = blockIdx.y, seg = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint8_t *f = flags + (size_t)u * L;
+  const uint8_t *f = flags ? flags + (size_t)u * L : nullptr;
   const int w_first = seg * kSegWords;
   const bool last_seg = seg == (int)gridDim.x - 1;
 
@@ -110,12 +112,14 @@ __global__ __launch_bounds__(kScanThreads) void ag_flag_scan_kernel(const uint8_
   for (int j = 0; j < WPW; ++j) {
     const int w = w_first + wave * WPW + j;
     const int t = w * 64 + lane;
-    fb[j] = (w < nw && t < L) ? f[t] : (uint8_t)0;
+    fb[j] = (w < nw && t < L) ? (flags ? f[t] : (uint8_t)1) : (uint8_t)0;
   }
   // kept tokens before the segment
   const int t_end = w_first * 64;  // <= L, a multiple of 1024
   int before = 0;
-  if ((reinterpret_cast<uintptr_t>(f) & 3) == 0) {
+  if (!flags) {
+    before = tid == 0 ? t_end : 0;
+  } else if ((reinterpret_cast<uintptr_t>(f) & 3) == 0) {
     const uint32_t *f4 = reinterpret_cast<const uint32_t *>(f);
     for (int i = tid; i < t_end / 4; i += kScanThreads) {
       const uint32_t x = f4[i];

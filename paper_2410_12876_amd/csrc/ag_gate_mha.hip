@@ -230,11 +230,6 @@ __global__ __launch_bounds__(256, 2) void ag_proj_gemm_kernel(const uint16_t *__
   }
 }
 
-__global__ void ag_fill_u8_kernel(uint8_t *p, size_t n, uint8_t value) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = value;
-}
-
 }  // namespace
 
 size_t ag_ws_gate_mha_bytes(int B, int L, int d_model, int hp, int H_f) {
@@ -247,7 +242,6 @@ size_t ag_ws_gate_mha_bytes(int B, int L, int d_model, int hp, int H_f) {
   ag_prefill_d128_plan(1024, B, L, hp, hp, count, &plan, &part);
   return 3 * ag_align256(tokens * hp * kDh * 2)      // Q', K', V'
          + ag_align256(tokens * hp * kDh * 2)        // attention output = gate features
-         + ag_align256((size_t)units * L)            // all-ones flags
          + ag_ws_scan_bytes(units, L) + ag_align256((size_t)(units + 1) * 8) + count.off +
          ag_ws_gate_bytes((int64_t)tokens, hp * kDh, H_f, AG_BF16) + 4096;
 }
@@ -260,7 +254,6 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
   const size_t per = (size_t)tokens * hp * kDh;
   uint16_t *qkv = ws.take<uint16_t>(3 * per);
   uint16_t *feat = ws.take<uint16_t>(per);
-  uint8_t *ones = ws.take<uint8_t>((size_t)units * L);
   uint64_t *words = ws.take<uint64_t>((size_t)units * nw);
   int32_t *blk_off = ws.take<int32_t>((size_t)units * (nw + 1));
   int64_t *row_off = ws.take<int64_t>(units + 1);
@@ -274,9 +267,8 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
             (const uint16_t *)w_qkv, tokens, d_model, N, L, hp, qkv, ag_proj_compact{});
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const size_t nf = (size_t)units * L;
-  hipLaunchKernelGGL(ag_fill_u8_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, s, ones, nf, (uint8_t)1);
-  if ((e = ag_launch_flag_scan(ctx, s, ones, units, L, words, blk_off, &plan)) != hipSuccess) return e;
+  // every token is kept (no flags to read): mask words, prefix counts and the launch plan of the attention kernel
+  if ((e = ag_launch_flag_scan(ctx, s, nullptr, units, L, words, blk_off, &plan)) != hipSuccess) return e;
   if ((e = ag_launch_slab_offsets(s, row_off, units, L)) != hipSuccess) return e;
   // every flag is set, so the compacted rows of a head are its K', V' rows themselves
   e = ag_launch_prefill_d128(s, qkv, qkv + per, qkv + 2 * per, words, blk_off, B, L, hp, hp, scale * 1.4426950408889634f,
