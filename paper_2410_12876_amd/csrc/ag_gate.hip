@@ -1,13 +1,15 @@
 // Gate (Eq. 3, Eq. 4): features [tokens, d_in] x W [d_in, H_f] -> logits -> keep flags.
 //
 // The product is a skinny GEMM (N = H_f <= 32) whose cost is reading the features once from HBM.  The bf16
-// path runs it on MFMA (v_mfma_f32_32x32x16_bf16, N padded to 32): every wave owns MT x 32 tokens and a slice
-// of the K range, streams its feature rows with 16-byte loads that together cover whole 128-byte lines, and
-// takes the matching W fragments either from W as stored, transposed on the way through LDS (fused kernel), or
-// from a pre-packed copy that stays in L2.  K is split over the waves of a workgroup.  With enough tokens one fused kernel does everything (ag_gate_fused_kernel).  With few tokens K is
-// also split over several workgroups; partial sums then go to the workspace and a second kernel adds them in a
-// fixed order (so flags are reproducible run to run), adds the bias, compares with the logit-space threshold and
-// writes the flags head-major.
+// path runs it on MFMA (v_mfma_f32_32x32x16_bf16, N padded to 32): every wave owns a tile of tokens and a slice
+// of the K range, fetches its feature rows as whole 128-byte lines (handed to the MFMA layout through LDS in the
+// fused kernels), and takes the matching W fragments either from W as stored, transposed on the way through LDS,
+// or from a pre-packed copy that stays in L2.  K is split over the waves of a workgroup.  With enough tokens one
+// fused kernel does everything (ag_gate_fused_kernel; ag_norm_gate_kernel when the normalisation of the input is
+// fused in as well).  With few tokens (decode-sized calls) K is also split over several workgroups of the simpler
+// ag_gate_mfma_kernel; partial sums then go to the workspace and a second kernel adds them in a fixed order (so
+// flags are reproducible run to run), adds the bias, compares with the logit-space threshold and writes the flags
+// head-major.
 #include "ag_internal.h"
 
 namespace {
@@ -87,8 +89,9 @@ __global__ __launch_bounds__(256) void ag_gate_mfma_kernel(const uint16_t *__res
   }
 }
 
-// One workgroup of 8 waves per 32 tokens and K split (grid.y splits; wave w takes 64-wide chunks w, w + 8, ... of
-// its split, four in flight), the 8 partial tiles added in wave order through LDS.  With one split the workgroup
+// One workgroup of 8 waves per tile of TOK = 32 or 16 tokens and K split (grid.y splits; wave w takes 64-wide
+// chunks w, w + 8, ... of its split, PF of them in flight), the 8 partial tiles added in wave order through LDS.
+// (TOK = 16: launches with fewer 32-token tiles than CUs; the upper half of the MFMA then repeats the lower.)  With one split the workgroup
 // goes on to bias, threshold, logits and head-major flags.  With several, each stores its 32x32 partial tile
 // (written through the caches, complete before its arrival is counted) and the split that arrives last adds all
 // of them in split order -- the same order whoever is last, so the flags are reproducible -- and finishes.
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(256) void ag_gate_mfma_kernel(const uint16_t *__res
 // RAW: W is taken as the caller stores it ([d_in, H_f] row-major, H_f a multiple of 4, 16-byte aligned).  A wave
 // copies the 64 rows of a chunk into its own 4 KiB of LDS and reads them back with the transposing LDS read,
 // which hands lane (n, kb) the eight rows kb*32 + step*8 + 0..7 of column n: the B operand that matches the
-// A operand's 16-byte feature loads.  Columns n >= H_f read whatever follows in LDS; they only reach output
+// A operand (lane = token m and half kb: features kb*32 + step*8 + 0..7).  Columns n >= H_f read whatever follows in LDS; they only reach output
 // columns that are never stored.  Otherwise wp holds the fragments prepared by ag_gate_pack_w.
 constexpr int kFusedWaves = 8;
 template <bool RAW, int PF, int TOK>

@@ -22,7 +22,11 @@
 //     chunk_tiles is a little above the average number of tiles per workgroup slot, measured on the device from
 //     the flags, so only an item that alone exceeds it is cut.  Items that fit one chunk write their output
 //     directly; the few long ones store unnormalised fp32 partial states in the workspace, and the chunk that
-//     arrives last (a per-item counter) combines them with its own registers and writes the rows.
+//     arrives last (a per-item counter) combines them, in an order that does not depend on who is last, and writes
+//     the rows.
+//   * Query rows come in and output rows go out as whole 256-byte rows (4 rows per instruction), turned into and
+//     out of the per-lane fragment layout through LDS; the scattered 16- and 8-byte pieces of the fragment layout
+//     would cost the texture path several times the address cycles.
 //   * Workgroups go to the 8 XCDs, and inside an XCD to its 4 shader engines, round-robin by their index
 //     (measured: workgroup i runs on XCD i % 8, engine (i / 8) % 4), so the index -> (head, query tile) map
 //     decides both L2 locality and balance.  All tiles of one head are given to one XCD (its K/V stay in that
