@@ -24,6 +24,12 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int kNP = 32;  // padded head count (MFMA N)
 
+// Swizzle key of row r of a wave's 32 x 128-byte hand-over buffer: the 16-byte piece p of the row is stored at
+// position p ^ xkey(r).  Rows alternate between the two halves of the 64 banks, so the 16 lanes that LDS serves
+// together (2 whole rows on the writing side, 16 rows at one piece index on the reading side) need 8 different
+// keys among rows of equal parity: bits 1..3 of the row.
+__device__ __forceinline__ int xkey(int r) { return (r >> 1) & 7; }
+
 // W [d_in, H_f] bf16 -> fragment order: [(chunk*4 + step)*64 + lane][8], lane = (n = lane%32, kb = lane/32),
 // element j = W[chunk*64 + kb*32 + step*8 + j][n]  (0 for n >= H_f).
 __global__ void ag_gate_pack_w(const uint16_t *__restrict__ w, int d_in, int H_f, uint16_t *__restrict__ wp) {
@@ -203,12 +209,12 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 2 ? 2 : 1) void ag_gate_fus
         wave_sync();  // the previous chunk's fragments have been read
 #pragma unroll
         for (int i = 0; i < NI; ++i)
-          *reinterpret_cast<AG_LDS u32x4 *>(xst + (8 * i + lr) * 128 + ((lp ^ lr) << 4)) =
+          *reinterpret_cast<AG_LDS u32x4 *>(xst + (8 * i + lr) * 128 + ((lp ^ xkey(8 * i + lr)) << 4)) =
               u32x4{a[p][i].x, a[p][i].y, a[p][i].z, a[p][i].w};
         wave_sync();  // the chunk's rows are there for every lane
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const u32x4 t = *reinterpret_cast<const AG_LDS u32x4 *>(xst + ma * 128 + (((kb * 4 + s) ^ (m & 7)) << 4));
+          const u32x4 t = *reinterpret_cast<const AG_LDS u32x4 *>(xst + ma * 128 + (((kb * 4 + s) ^ xkey(ma)) << 4));
           a[p][s] = make_uint4(t[0], t[1], t[2], t[3]);
         }
 #pragma unroll
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, TOK == 16 ? 2 : 1) void ag_norm_g
         }
         const u32x4 xv = {xd[0], xd[1], xd[2], xd[3]};
         if (8 * i + lr < rows) __builtin_amdgcn_raw_buffer_store_b128(xv, x_rsrc, row_off[i], c * 128, 0);
-        *reinterpret_cast<AG_LDS u32x4 *>(xst + (8 * i + lr) * 128 + ((lp ^ lr) << 4)) = xv;
+        *reinterpret_cast<AG_LDS u32x4 *>(xst + (8 * i + lr) * 128 + ((lp ^ xkey(8 * i + lr)) << 4)) = xv;
       }
     }
     uint4(&bw)[4] = b[p % 3];
@@ -433,7 +439,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, TOK == 16 ? 2 : 1) void ag_norm_g
       u32x4 af[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s)
-        af[s] = *reinterpret_cast<const AG_LDS u32x4 *>(xst + ma * 128 + (((kb * 4 + s) ^ (m & 7)) << 4));
+        af[s] = *reinterpret_cast<const AG_LDS u32x4 *>(xst + ma * 128 + (((kb * 4 + s) ^ xkey(ma)) << 4));
 #pragma unroll
       for (int s = 0; s < 4; ++s)
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[s]),
