@@ -139,7 +139,7 @@ ag_status ag_gate(ag_ctx *ctx, void *hip_stream, const void *feat, ag_dtype dtyp
  * in one pass over h: x_out is written for the projections that follow and the gate needs no second read of it.
  * h, x_out [B, L, d_in], norm_w [d_in] and w_gate [d_in, H_f] bf16, 16-byte aligned (w_gate only for speed);
  * x_out may be h itself (in-place normalisation).  bias fp32 [H_f]; logits_out fp32 [B, L, H_f] may be NULL;
- * flags_out uint8 [B, H_f, L].  Built for bf16, d_in % 64 == 0, d_in <= 4096, eps > 0 (else AG_EUNSUPPORTED /
+ * flags_out uint8 [B, H_f, L].  Built for bf16, d_in % 64 == 0, d_in <= 8192, eps > 0 (else AG_EUNSUPPORTED /
  * AG_EINVAL).  Needs no more workspace than ag_gate on the same sizes.
  */
 ag_status ag_rmsnorm_gate(ag_ctx *ctx, void *hip_stream, const void *h, ag_dtype dtype, int B, int L, int d_in,

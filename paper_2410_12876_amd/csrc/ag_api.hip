@@ -249,8 +249,8 @@ ag_status ag_rmsnorm_gate(ag_ctx *ctx, void *hip_stream, const void *h, ag_dtype
   AG_REQUIRE(n_sink >= 0, AG_EINVAL, "ag_rmsnorm_gate: n_sink is negative");
   AG_REQUIRE(dtype_ok(dtype), AG_EINVAL, "ag_rmsnorm_gate: unknown dtype %d", (int)dtype);
   AG_REQUIRE(dtype == AG_BF16, AG_EUNSUPPORTED, "ag_rmsnorm_gate: only bf16 is built");
-  AG_REQUIRE(d_in % 64 == 0 && d_in <= 4096, AG_EUNSUPPORTED,
-             "ag_rmsnorm_gate: d_in must be a multiple of 64 and at most 4096 (got %d)", d_in);
+  AG_REQUIRE(d_in % 64 == 0 && d_in <= 8192, AG_EUNSUPPORTED,
+             "ag_rmsnorm_gate: d_in must be a multiple of 64 and at most 8192 (got %d)", d_in);
   AG_REQUIRE(H_f <= 32, AG_EUNSUPPORTED, "ag_rmsnorm_gate: H_f = %d exceeds 32", H_f);
   AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_rmsnorm_gate: L = %d exceeds %d", L, kMaxL);
   AG_REQUIRE(((uintptr_t)h & 15) == 0 && ((uintptr_t)x_out & 15) == 0 && ((uintptr_t)norm_w & 15) == 0, AG_EINVAL,

@@ -284,7 +284,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 2 ? 2 : 1) void ag_gate_fus
 
 // RMS normalisation fused with the gate: x = h / sqrt(mean_c h^2 + eps) * g, rounded once to bf16, written out for
 // the projections that follow, and multiplied by W from the same registers, so the gate costs no second read of x.
-// One workgroup of 8 waves per 32 tokens.  Wave w owns the 64-feature chunks w, w + 8, ... (at most kNormChunks of
+// One workgroup of 8 waves per 32 tokens.  Wave w owns the 64-feature chunks w, w + 8, ... (at most NCH of
 // them: d_in <= 4096) of all 32 rows and keeps them in registers for the whole kernel, so all loads of the tile are
 // in flight at once.  A chunk is one 128-byte line per row; a load or store instruction moves 8 whole lines (lane
 // -> row 8 i + lane / 8, 16-byte piece lane % 8).  The squares are summed per lane, over the 8 lanes of a row and
@@ -294,15 +294,14 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 2 ? 2 : 1) void ag_gate_fus
 // layout, the W fragments and the order of the MFMAs (chunks ascending per wave, then the waves in order) are
 // those of ag_gate_fused_kernel with one K split, so the logits are those ag_gate gives on the stored x bit for
 // bit whenever that kernel runs unsplit.
-constexpr int kNormChunks = 8;
-template <bool RAW, int TOK>
+template <bool RAW, int TOK, int NCH>  // NCH = chunks a wave holds: d_in <= 8 waves x NCH x 64 features
 __global__ __launch_bounds__(64 * kFusedWaves, TOK == 16 ? 2 : 1) void ag_norm_gate_kernel(
     const uint16_t *h, const uint16_t *__restrict__ g, float eps, const uint4 *__restrict__ wp,
     int64_t tokens, int d_in, int L, int H_f, const float *__restrict__ bias, float thr, int n_sink,
     uint16_t *x_out, float *__restrict__ logits, uint8_t *__restrict__ flags) {
   // [wave][4 KiB]: the wave's hand-over buffer (chunk of x, then chunk of W), afterwards its 32 x 32 fp32 partial tile
   __shared__ __attribute__((aligned(16))) uint8_t wst[kFusedWaves][2][4096];
-  __shared__ __attribute__((aligned(16))) uint16_t g_l[kFusedWaves * kNormChunks * 64];
+  __shared__ __attribute__((aligned(16))) uint16_t g_l[kFusedWaves * NCH * 64];
   __shared__ float ssq_l[kFusedWaves][32];
   __shared__ uint8_t fl[kNP][32];
   const int lane = threadIdx.x & 63;
@@ -323,9 +322,9 @@ __global__ __launch_bounds__(64 * kFusedWaves, TOK == 16 ? 2 : 1) void ag_norm_g
 #pragma unroll
   for (int i = 0; i < NI; ++i) row_off[i] = min(8 * i + lr, rows - 1) * d_in * 2 + lp * 16;
   auto to_u4 = [](u32x4 v) { return make_uint4(v[0], v[1], v[2], v[3]); };
-  uint4 a[kNormChunks][NI];
+  uint4 a[NCH][NI];
 #pragma unroll
-  for (int p = 0; p < kNormChunks; ++p) {
+  for (int p = 0; p < NCH; ++p) {
     const int c = min(wave + kFusedWaves * p, nchunks - 1);
 #pragma unroll
     for (int i = 0; i < NI; ++i) a[p][i] = to_u4(__builtin_amdgcn_raw_buffer_load_b128(h_rsrc, row_off[i], c * 128, 0));
@@ -346,15 +345,15 @@ __global__ __launch_bounds__(64 * kFusedWaves, TOK == 16 ? 2 : 1) void ag_norm_g
   uint4 b[3][4];
   load_w(b[0], 0);
   load_w(b[1], 1);
-  // the normalisation weights: 16 bytes per thread cover 4096 of them
-  if ((int)threadIdx.x * 8 < d_in)
-    *reinterpret_cast<uint4 *>(&g_l[threadIdx.x * 8]) = *reinterpret_cast<const uint4 *>(g + threadIdx.x * 8);
+  // the normalisation weights: 16 bytes per thread and round cover 4096 of them
+  for (int i = (int)threadIdx.x * 8; i < d_in; i += 64 * kFusedWaves * 8)
+    *reinterpret_cast<uint4 *>(&g_l[i]) = *reinterpret_cast<const uint4 *>(g + i);
 
   float ssq[NI];
 #pragma unroll
   for (int i = 0; i < NI; ++i) ssq[i] = 0.f;
 #pragma unroll
-  for (int p = 0; p < kNormChunks; ++p)
+  for (int p = 0; p < NCH; ++p)
     if (wave + kFusedWaves * p < nchunks) {
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
@@ -395,9 +394,9 @@ __global__ __launch_bounds__(64 * kFusedWaves, TOK == 16 ? 2 : 1) void ag_norm_g
 #pragma unroll
   for (int r16 = 0; r16 < 16; ++r16) acc[r16] = 0.f;
 #pragma unroll
-  for (int p = 0; p < kNormChunks; ++p) {
+  for (int p = 0; p < NCH; ++p) {
     __builtin_amdgcn_sched_barrier(0);  // one chunk at a time: interleaving them costs more registers than it hides
-    if (p + 2 < kNormChunks) load_w(b[(p + 2) % 3], p + 2);
+    if (p + 2 < NCH) load_w(b[(p + 2) % 3], p + 2);
     const bool valid = wave + kFusedWaves * p < nchunks;  // wave-uniform
     const int c = wave + kFusedWaves * p;
     if (valid) {
@@ -656,17 +655,19 @@ hipError_t ag_launch_norm_gate(ag_ctx *ctx, hipStream_t s, const void *h, int B,
     hipLaunchKernelGGL(ag_gate_pack_w, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t *)w, d_in, H_f, wp);
   }
   // tiles of 16 tokens while 32-token tiles would leave CUs without a workgroup (measured at 4096 features: 4096
-  // tokens 17.8 us against 22.0 us; from 8192 tokens on the 32-token tiles are 5-10 % faster)
-  const bool tok16 = (tokens + 31) / 32 < ctx->num_cu;
+  // tokens 17.8 us against 22.0 us; from 8192 tokens on the 32-token tiles are 5-10 % faster); rows of more than
+  // 4096 features always take them, with 16 chunks per wave (the same registers as 32 tokens x 8 chunks)
+  const bool wide = d_in > 4096;
+  const bool tok16 = wide || (tokens + 31) / 32 < ctx->num_cu;
   const dim3 grid((unsigned)((tokens + (tok16 ? 15 : 31)) / (tok16 ? 16 : 32))), block(64 * kFusedWaves);
   const ag_evpair ev = ag_time_kernel(ctx, AG_K_NORM_GATE);
-#define AG_NORM_GATE(RAWV, TOKV, WPTR)                                                                              \
-  AG_LAUNCH(ev, (ag_norm_gate_kernel<RAWV, TOKV>), grid, block, 0, s, (const uint16_t *)h, (const uint16_t *)g, eps, \
+#define AG_NORM_GATE(RAWV, TOKV, NCHV, WPTR)                                                                              \
+  AG_LAUNCH(ev, (ag_norm_gate_kernel<RAWV, TOKV, NCHV>), grid, block, 0, s, (const uint16_t *)h, (const uint16_t *)g, eps, \
             (const uint4 *)(WPTR), tokens, d_in, L, H_f, bias, thr, n_sink, (uint16_t *)x_out, logits, flags)
   if (raw_w) {
-    if (tok16) AG_NORM_GATE(true, 16, w); else AG_NORM_GATE(true, 32, w);
+    if (wide) AG_NORM_GATE(true, 16, 16, w); else if (tok16) AG_NORM_GATE(true, 16, 8, w); else AG_NORM_GATE(true, 32, 8, w);
   } else {
-    if (tok16) AG_NORM_GATE(false, 16, wp); else AG_NORM_GATE(false, 32, wp);
+    if (wide) AG_NORM_GATE(false, 16, 16, wp); else if (tok16) AG_NORM_GATE(false, 16, 8, wp); else AG_NORM_GATE(false, 32, 8, wp);
   }
 #undef AG_NORM_GATE
   return hipGetLastError();

@@ -73,9 +73,9 @@ def test_error_paths_without_device(lib):
     expect(ag.AG_EINVAL, ag.ag_rmsnorm_gate, ctx, hb, None, 1e-5, wb, bias, 0.5, 0, hb.clone(), None, flags, stream=0)
     expect(ag.AG_EUNSUPPORTED, ag.ag_rmsnorm_gate, ctx, x, w[:, 0].contiguous(), 1e-5, w, bias, 0.5, 0, x.clone(), None,
            flags, stream=0)                                                                      # fp32 is not built
-    big = xb.new_zeros(1, 8, 4160)
-    expect(ag.AG_EUNSUPPORTED, ag.ag_rmsnorm_gate, ctx, big, xb.new_zeros(4160), 1e-5, xb.new_zeros(4160, 4), bias, 0.5,
-           0, big.clone(), None, flags, stream=0)                                                # d_in > 4096
+    big = xb.new_zeros(1, 8, 8256)
+    expect(ag.AG_EUNSUPPORTED, ag.ag_rmsnorm_gate, ctx, big, xb.new_zeros(8256), 1e-5, xb.new_zeros(8256, 4), bias, 0.5,
+           0, big.clone(), None, flags, stream=0)                                                # d_in > 8192
 
     q = torch.zeros(1, 4, 8, 64)
     k = torch.zeros(1, 2, 8, 64)

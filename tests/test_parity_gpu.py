@@ -173,7 +173,8 @@ def check_rmsnorm_gate(h, g, eps, w, bias, tau, n_sink, misalign=False, what="")
 @pytest.mark.parametrize("B,L,d,H,tau,n_sink,misalign", [
     (1, 100, 256, 4, 0.5, 0, False), (2, 77, 512, 8, 0.3, 2, False), (1, 1, 64, 32, 0.5, 0, False),
     (1, 33, 4096, 32, 0.5, 1, False), (3, 333, 1024, 6, 0.7, 1, False), (1, 2100, 2048, 32, 0.5, 0, False),
-    (1, 64, 3072, 12, 0.5, 0, True), (2, 50, 4032, 20, 0.4, 0, False)])
+    (1, 64, 3072, 12, 0.5, 0, True), (2, 50, 4032, 20, 0.4, 0, False), (1, 40, 8192, 32, 0.5, 0, False),
+    (2, 300, 5120, 8, 0.5, 1, False), (1, 70, 6144, 6, 0.5, 0, False)])
 def test_rmsnorm_gate_shapes(B, L, d, H, tau, n_sink, misalign):
     """Feature counts that fill all, some and (d = 64, 256) not even one chunk per wave, head counts that take the
     weights as stored and pre-packed, ragged last tiles; rows of very different scale, an all-zero row and a row with
