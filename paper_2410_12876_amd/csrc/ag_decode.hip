@@ -117,20 +117,22 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
     if (meta_lds) { s_len[u] = n_u; s_ro[u] = row_off[u]; }
     sum += (n_u + kChunk - 1) / kChunk;
   }
-  scan[tid] = sum;
-  __syncthreads();
-  for (int d = 1; d < 256; d <<= 1) {
-    int32_t add = tid >= d ? scan[tid - d] : 0;
-    __syncthreads();
-    scan[tid] += add;
-    __syncthreads();
+  // exclusive scan over the 256 threads: inside a wave by shuffles, across the four waves through LDS (one barrier)
+  int32_t incl = sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int32_t up = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += up;
   }
-  int32_t run = scan[tid] - sum;
+  if (lane == 63) scan[wave] = incl;
+  __syncthreads();
+  int32_t run = incl - sum;
+  for (int w = 0; w < wave; ++w) run += scan[w];
   for (int u = u0; u < u1; ++u) {
     item_off[u] = run;
     run += (unit_len(len, row_off, u) + kChunk - 1) / kChunk;
   }
-  if (tid == 255) item_off[U] = scan[255];
+  if (tid == 255) item_off[U] = scan[0] + scan[1] + scan[2] + scan[3];
   __syncthreads();
   const int n_items = item_off[U];
   if (blockIdx.x == 0)
