@@ -97,8 +97,9 @@ ag_status ag_poll_error(ag_ctx *ctx, void *hip_stream);
  * on the call's stream: the main kernels (fused gate, scan + compaction, prefill, decode partial and merge,
  * projection) have them attached to the launch itself, so the duration is the kernel's own; the remaining
  * launches are bracketed by records on the stream.  Up to 1024 launches per kernel id are remembered; later
- * ones are not timed.  Leave timing off while the stream is being captured into a HIP graph.  ag_timing_enable(ctx, 1) resets the counts; ag_timing_read waits for the recorded events and
- * returns the summed duration and the number of launches of one kernel id in [0, ag_timing_kernels()).
+ * ones are not timed.  Leave timing off while the stream is being captured into a HIP graph.
+ * ag_timing_enable(ctx, 1) resets the counts; ag_timing_read waits for the recorded events and returns the summed
+ * duration and the number of launches of one kernel id in [0, ag_timing_kernels()).
  * Ids: 0 gate (GEMM), 1 gate_finalize, 2 flag_scan, 3 compact, 4 prefill, 5 decode_partial, 6 decode_merge,
  * 7 mha_proj, 8 mha_attn, 9 norm_gate; ag_timing_kernel_name gives the names.
  */
