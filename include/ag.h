@@ -240,6 +240,25 @@ ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const voi
                          const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache, void *out);
 
 /*
+ * ag_decode_attn for callers that cannot allocate device memory or be handed a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same
+ * results as ag_decode_attn, but the per-item records that the two decode kernels exchange live in a static
+ * device array of the library (ag_decode_static_scratch_bytes() = 16 MiB per GPU, held until the process ends)
+ * instead of the context's workspace; the call allocates and frees nothing and a context made with
+ * workspace_bytes = 0 is enough.  The array's device address is looked up once per GPU inside ag_create.
+ * A cache needs ag_decode_scratch_bytes(cache, Hq) bytes (about 4 (D + 2) (Hq / Hkv) bytes per 128 cache rows
+ * of total_rows, plus as much per unit); a cache that needs more than the array holds is rejected with
+ * AG_EWORKSPACE and nothing is launched.  Nothing in the array has to be zero between calls.  Every call on one
+ * GPU shares that GPU's array, whatever its context: two such calls that overlap on the device race; keep them on
+ * one stream or order them with events.
+ */
+size_t ag_decode_static_scratch_bytes(void);
+size_t ag_decode_scratch_bytes(const ag_kv_cache *cache, int Hq);
+ag_status ag_decode_attn_static(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                                const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache,
+                                void *out);
+
+/*
  * Decoding with the recent-token window (Table 6 of the appendix, "keep recent tokens"): the tokens at the n_recent - 1 positions
  * before the new one stay visible whatever their flag.  The evicted ones are not in the cache, so the last
  * n_recent tokens of every unit live in a small ring, slot = position % n_recent (caller-owned device memory):

@@ -25,7 +25,7 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
            "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_rmsnorm_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
-           "ag_compact_prefill_attn", "ag_project_compact_kv", "ag_project_compact_workspace_bytes", "ag_decode_attn", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
+           "ag_compact_prefill_attn", "ag_project_compact_kv", "ag_project_compact_workspace_bytes", "ag_decode_attn", "ag_decode_attn_static", "ag_decode_static_scratch_bytes", "ag_decode_scratch_bytes", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
 
 
 class ag_recent_ring(C.Structure):
@@ -100,6 +100,12 @@ def load() -> C.CDLL:
     lib.ag_project_compact_kv.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, C.POINTER(ag_kv_cache)]
     lib.ag_decode_attn.restype = C.c_int
     lib.ag_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache), vp]
+    lib.ag_decode_attn_static.restype = C.c_int
+    lib.ag_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, f32, C.POINTER(ag_kv_cache), vp]
+    lib.ag_decode_static_scratch_bytes.restype = C.c_size_t
+    lib.ag_decode_static_scratch_bytes.argtypes = []
+    lib.ag_decode_scratch_bytes.restype = C.c_size_t
+    lib.ag_decode_scratch_bytes.argtypes = [C.POINTER(ag_kv_cache), i32]
     lib.ag_gate_mha_workspace_bytes.restype = C.c_size_t
     lib.ag_gate_mha_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
     lib.ag_gate_mha.restype = C.c_int
@@ -285,6 +291,22 @@ def ag_decode_attn(ctx: Context, q, k_new, v_new, new_flags, pos: int, scale: fl
     Hq = q.shape[1]
     ctx._check(ctx._lib.ag_decode_attn(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k_new), _ptr(v_new),
                                        _ptr(new_flags), pos, Hq, scale, C.byref(cache.c), _ptr(out)))
+
+
+def ag_decode_attn_static(ctx: Context, q, k_new, v_new, new_flags, pos: int, scale: float, cache: KVCache, out,
+                          stream=None) -> None:
+    """ag_decode_attn out of the library's static per-GPU scratch array: allocates nothing, needs no workspace."""
+    Hq = q.shape[1]
+    ctx._check(ctx._lib.ag_decode_attn_static(ctx._h, _stream_ptr(stream), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                              _ptr(new_flags), pos, Hq, scale, C.byref(cache.c), _ptr(out)))
+
+
+def decode_static_scratch_bytes() -> int:
+    return int(load().ag_decode_static_scratch_bytes())
+
+
+def decode_scratch_bytes(cache: KVCache, Hq: int) -> int:
+    return int(load().ag_decode_scratch_bytes(C.byref(cache.c), Hq))
 
 
 class RecentRing:

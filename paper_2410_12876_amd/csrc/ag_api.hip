@@ -83,6 +83,7 @@ ag_status ag_create(ag_ctx **out, int device, size_t workspace_bytes) {
       ctx->gate_tickets = reinterpret_cast<int32_t *>(ctx->ws + ctx->ws_bytes + 256);
       e = hipMemset(ctx->d_err, 0, kTailBytes);
     }
+    if (e == hipSuccess) e = ag_static_scratch(device, &ctx->static_scratch);
     if (e != hipSuccess) {
       if (ctx->ws) (void)hipFree(ctx->ws);
       delete ctx;
@@ -485,9 +486,44 @@ ag_status ag_decode_attn(ag_ctx *ctx, void *hip_stream, const void *q, const voi
   return ag_decode_attn_recent(ctx, hip_stream, q, k_new, v_new, new_flags, pos, Hq, scale, cache, nullptr, out);
 }
 
+}  // extern "C"
+
+namespace {
+// ag_decode_attn[_recent] (records in the context's workspace) and ag_decode_attn_static (records in the library's
+// static per-GPU scratch array: nothing of the workspace is touched).
+ag_status decode_common(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                        const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache,
+                        ag_recent_ring *ring, void *out, bool static_scratch);
+}  // namespace
+
+extern "C" {
+
 ag_status ag_decode_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
                                 const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache,
                                 ag_recent_ring *ring, void *out) {
+  return decode_common(ctx, hip_stream, q, k_new, v_new, new_flags, pos, Hq, scale, cache, ring, out, false);
+}
+
+size_t ag_decode_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+size_t ag_decode_scratch_bytes(const ag_kv_cache *cache, int Hq) {
+  if (!cache || cache->B <= 0 || cache->Hkv <= 0 || cache->D <= 0 || Hq <= 0 || Hq % cache->Hkv || cache->total_rows < 0)
+    return 0;
+  return ag_ws_decode_bytes(cache->B * cache->Hkv, Hq / cache->Hkv, cache->D, cache->total_rows);
+}
+
+ag_status ag_decode_attn_static(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                                const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache,
+                                void *out) {
+  return decode_common(ctx, hip_stream, q, k_new, v_new, new_flags, pos, Hq, scale, cache, nullptr, out, true);
+}
+
+}  // extern "C"
+
+namespace {
+ag_status decode_common(ag_ctx *ctx, void *hip_stream, const void *q, const void *k_new, const void *v_new,
+                        const uint8_t *new_flags, int pos, int Hq, float scale, ag_kv_cache *cache,
+                        ag_recent_ring *ring, void *out, bool static_scratch) {
   if (!ctx) return AG_EINVAL;
   AG_REQUIRE(q && k_new && v_new && cache && out, AG_EINVAL, "ag_decode_attn: null pointer");
   ag_status st = check_cache(ctx, cache);
@@ -502,11 +538,17 @@ ag_status ag_decode_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, co
   const int G = Hq / cache->Hkv, units = cache->B * cache->Hkv;
   AG_REQUIRE(ag_decode_supported(cache->dtype, cache->D, G, units), AG_EUNSUPPORTED,
              "ag_decode_attn: unsupported dtype/D/group/units (%d, %d, %d, %d)", (int)cache->dtype, cache->D, G, units);
-  AG_REQUIRE(ag_ws_decode_bytes(units, G, cache->D, cache->total_rows) <= ctx->ws_bytes, AG_EWORKSPACE,
-             "ag_decode_attn: workspace of %zu bytes is too small", ctx->ws_bytes);
+  const size_t need = ag_ws_decode_bytes(units, G, cache->D, cache->total_rows);
+  if (static_scratch)
+    AG_REQUIRE(need <= kStaticScratchBytes, AG_EWORKSPACE,
+               "ag_decode_attn_static: this cache needs %zu bytes of scratch, the static array holds %zu "
+               "(ag_decode_scratch_bytes; use ag_decode_attn with a workspace instead)", need, kStaticScratchBytes);
+  else
+    AG_REQUIRE(need <= ctx->ws_bytes, AG_EWORKSPACE, "ag_decode_attn: workspace of %zu bytes is too small",
+               ctx->ws_bytes);
   st = need_device(ctx);
   if (st != AG_OK) return st;
-  ws_cursor ws = cursor(ctx);
+  ws_cursor ws = static_scratch ? ws_cursor{ctx->static_scratch, kStaticScratchBytes, 0, true} : cursor(ctx);
   hipError_t e = ag_launch_decode(ctx, (hipStream_t)hip_stream, q, k_new, v_new, new_flags, pos, cache->B, Hq, cache->Hkv,
                                   cache->D, cache->dtype, scale, cache->k, cache->v, cache->idx, cache->row_off,
                                   cache->len, cache->total_rows, out, ws, ring_dev(ring));
@@ -514,5 +556,4 @@ ag_status ag_decode_attn_recent(ag_ctx *ctx, void *hip_stream, const void *q, co
   AG_HIP(e);
   return AG_OK;
 }
-
-}  // extern "C"
+}  // namespace

@@ -7,7 +7,15 @@
 // group, and the states are merged through LDS into one (max, sum, weighted-V) record per item and head.
 // A second kernel merges the records of each (batch, query head) with the new token's own key/value -- the
 // diagonal of Eq. 5 -- normalises, and appends the new row to the cache when its flag says so.
+#include <mutex>
+
 #include "ag_internal.h"
+
+// Scratch of ag_decode_attn_static, the entry point for callers that cannot allocate: the per-item records the
+// two decode kernels exchange live here instead of in a context's workspace.  One copy per GPU, held until the
+// process ends.  In host code this name is only a stand-in for the symbol; the device address comes from
+// hipGetSymbolAddress (ag_static_scratch below) and is what every launch receives.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -473,6 +481,27 @@ size_t ag_ws_decode_bytes(int units, int G, int D, int64_t cache_rows) {
   const int64_t items = max_items(units, cache_rows);
   return ag_align256((size_t)(units + 1) * 4) + 2 * ag_align256((size_t)items * G * 4) +
          ag_align256((size_t)items * G * D * 4);
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device (with that device current) and kept.
+hipError_t ag_static_scratch(int device, char **ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static char *known[kMaxDevices];
+  *ptr = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!known[device]) {
+    hipError_t e = hipSetDevice(device);
+    if (e != hipSuccess) return e;
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    known[device] = static_cast<char *>(p);
+  }
+  *ptr = known[device];
+  return hipSuccess;
 }
 
 bool ag_decode_supported(ag_dtype dt, int D, int G, int units) {

@@ -12,6 +12,7 @@ enum { AG_K_GATE = 0, AG_K_GATE_FINALIZE, AG_K_FLAG_SCAN, AG_K_COMPACT, AG_K_PRE
        AG_K_DECODE_MERGE, AG_K_MHA_PROJ, AG_K_MHA_ATTN, AG_K_NORM_GATE, AG_K_COUNT };
 constexpr int kTimerSlots = 1024;  // launches remembered per kernel id
 constexpr int kGateTickets = 1024; // token tiles whose K splits can be counted
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;  // per-GPU static scratch of ag_decode_attn_static
 
 struct ag_timer {
   hipEvent_t *start, *stop;  // kTimerSlots each, created on first enable
@@ -25,6 +26,7 @@ struct ag_ctx {
   size_t ws_bytes;
   int32_t *d_err;   // sticky device error word (bit 0: cache capacity overflow)
   int32_t *gate_tickets;  // [kGateTickets] arrival counters of the gate's K splits: zero between launches
+  char *static_scratch;   // this device's copy of the library's static scratch array (ag_decode_attn_static)
   bool timing;
   ag_timer timers[AG_K_COUNT];
   char err[320];
@@ -168,6 +170,9 @@ hipError_t ag_launch_decode(ag_ctx *ctx, hipStream_t s, const void *q, const voi
                             const uint8_t *new_flags, int pos, int B, int Hq, int Hkv, int D, ag_dtype dt,
                             float scale, void *kc, void *vc, int32_t *idx, const int64_t *row_off, int32_t *len,
                             int64_t total_rows, void *out, ws_cursor &ws, ag_ring_dev ring);
+
+// Device address of the static scratch array (kStaticScratchBytes) on `device`; looked up once per device.
+hipError_t ag_static_scratch(int device, char **ptr);
 
 // Ring <- the last min(L, n) prompt tokens of every unit (k, v [units, L, D], flags [units, L]).
 hipError_t ag_launch_ring_fill(hipStream_t s, const void *k, const void *v, const uint8_t *flags, int units, int L,

@@ -98,6 +98,13 @@ def test_error_paths_without_device(lib):
     expect(ag.AG_EHIP, ag.ag_decode_attn, ctx, qd, kn, kn, None, 8, 0.125, cache, qd.clone(), stream=0)
     expect(ag.AG_EINVAL, ag.ag_decode_attn, ctx, torch.zeros(1, 3, 64), kn, kn, None, 8, 0.125, cache, qd.clone(), stream=0)
     expect(ag.AG_EINVAL, ag.ag_decode_attn, ctx, qd, kn, kn, None, 8, -1.0, cache, qd.clone(), stream=0)
+    # the entry point that allocates nothing: same validation, and a cache beyond its static array is refused
+    expect(ag.AG_EHIP, ag.ag_decode_attn_static, ctx, qd, kn, kn, None, 8, 0.125, cache, qd.clone(), stream=0)
+    expect(ag.AG_EINVAL, ag.ag_decode_attn_static, ctx, qd, kn, None, None, 8, 0.125, cache, qd.clone(), stream=0)
+    huge = make_cache()
+    huge.c.total_rows = 1 << 24
+    assert ag.decode_scratch_bytes(huge, 4) > ag.decode_static_scratch_bytes() == 16 << 20
+    expect(ag.AG_EWORKSPACE, ag.ag_decode_attn_static, ctx, qd, kn, kn, None, 8, 0.125, huge, qd.clone(), stream=0)
     ctx.close()
 
 
