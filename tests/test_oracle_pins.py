@@ -64,6 +64,29 @@ def test_eq5_mask_fixture_matches_oracle_visibility():
     np.testing.assert_allclose(out, M / M.sum(axis=1, keepdims=True), rtol=0, atol=1e-15)
 
 
+def test_recent_window_mask_fixture_fixes_the_width_convention():
+    """Table 6 (appendix "More Ablation"): "n recent tokens" counts the current token (setting (1), the diagonal
+    alone, is one recent token).  The hand-written mask for 3 recent tokens pins the oracle's n_recent argument,
+    and the helper eq5_mask used by the dense comparisons below, to that reading: off by one in either direction
+    changes rows 3 to 5 of the fixture."""
+    flags = np.array([1, 0, 0, 1, 0, 0], dtype=np.uint8)
+    M = np.array(read_rows("eq5_mask_recent3_n6.txt", int), dtype=np.float64)
+    assert M.shape == (6, 6)
+    assert np.array_equal(M, eq5_mask(flags, 3))
+    assert not np.array_equal(M, eq5_mask(flags, 2)) and not np.array_equal(M, eq5_mask(flags, 4))
+    L = 6
+    q = np.zeros((1, 1, L, L), dtype=np.float32)
+    v = np.eye(L, dtype=np.float32).reshape(1, 1, L, L)
+    out = oracle.prefill_attn(q, rnd(14, 1, 1, L, L), v, flags.reshape(1, 1, L), 1.0, n_recent=3)[0, 0]
+    assert np.array_equal(out > 0, M > 0)
+    np.testing.assert_allclose(out, M / M.sum(axis=1, keepdims=True), rtol=0, atol=1e-15)
+    rows = oracle.prefill_rows(q, rnd(14, 1, 1, L, L), v, flags.reshape(1, 1, L), 1.0, np.arange(L), n_recent=3)[0, 0]
+    np.testing.assert_allclose(rows, out, rtol=0, atol=0)
+    # one recent token is Eq. 5 itself
+    one = oracle.prefill_attn(q, rnd(14, 1, 1, L, L), v, flags.reshape(1, 1, L), 1.0, n_recent=1)[0, 0]
+    assert np.array_equal(one > 0, eq5_mask(flags) > 0)
+
+
 def test_uniform_attention_fixture():
     want = np.array(read_rows("uniform_attention_n5.txt", lambda s: float(Fraction(s))))
     flags = np.array([1, 0, 1, 0, 0], dtype=np.uint8).reshape(1, 1, 5)
