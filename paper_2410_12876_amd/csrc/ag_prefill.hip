@@ -35,6 +35,18 @@ __device__ __forceinline__ int cnt_at(const uint64_t *__restrict__ words, const 
   return bo[j >> 6] + __popcll(w & ((1ull << (j & 63)) - 1ull));
 }
 
+// Keep bits of mask word t of a unit restricted to the tokens that are among the unit's len_u compacted rows: all
+// kept ones, unless the cache overflowed -- a kept token that found no room is not there, and the recent-token band
+// must show it like an evicted one.
+__device__ __forceinline__ uint64_t in_cache_bits(const uint64_t *__restrict__ words, const int32_t *__restrict__ bo,
+                                                  int t, int len_u) {
+  uint64_t w = words[t];
+  const int room = len_u - bo[t];
+  if (room <= 0) return 0;
+  while (__popcll(w) > room) w &= ~(1ull << (63 - __clzll(w)));  // (never entered without an overflow)
+  return w;
+}
+
 // GB = query heads of one KV group handled by a workgroup (one per wave); 4/GB query sub-tiles of 32.
 template <int D, int GB>
 __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
@@ -50,6 +62,7 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
   constexpr int VSTR = kBN + 8;    // LDS row stride of the V^T tile
   __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KSTR];
   __shared__ __attribute__((aligned(16))) uint16_t Vt[D * VSTR];
+  __shared__ uint32_t nf_rows[3][2];  // per band tile: rows whose value row held a NaN or an infinity (see `tile`)
 
   const int G = Hq / Hkv;
   const int HB = G / GB;  // head blocks per KV group
@@ -67,10 +80,14 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
   const int32_t *bo = blk_off + (size_t)u * (nw + 1);
   // kept rows, clamped to the unit's slab so that an overflowed cache can never be read out of bounds
   const int len_u = (int)min((int64_t)bo[nw], row_off[u + 1] - row_off[u]);
-  const int cnt_q = cnt_at(wu, bo, jq);
-  const int cnt_wave_lo = cnt_at(wu, bo, min(j0, L - 1));
-  const int cnt_wave_hi = j0 < L ? cnt_at(wu, bo, min(j0 + 31, L - 1)) : 0;
-  const int cnt_blk = cnt_at(wu, bo, min(qtile * BM + BM - 1, L - 1));
+  // (boundaries clamped to the rows the cache holds: after a capacity overflow the rows that did not fit are not
+  // there -- their tokens count as evicted -- and the zero rows a tile is padded with are never attended)
+  const int cnt_q = min(cnt_at(wu, bo, jq), len_u);
+  const int cnt_wave_lo = min(cnt_at(wu, bo, min(j0, L - 1)), len_u);
+  const int cnt_wave_hi = j0 < L ? min(cnt_at(wu, bo, min(j0 + 31, L - 1)), len_u) : 0;
+  const int cnt_blk = min(cnt_at(wu, bo, min(qtile * BM + BM - 1, L - 1)), len_u);
+  if (tid < 6) nf_rows[tid >> 1][tid & 1] = 0u;  // ordered before their first use by the barriers of `tile`
+  bool poisoned = false;
 
   const size_t qrow = ((size_t)(b * Hq + head) * L + jq) * D;
   const size_t kvrow = ((size_t)u * L + jq) * D;
@@ -114,7 +131,10 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
   // (band == false) hide keys at or past the query's boundary cnt_q.  Band tiles (band == true) come from the
   // uncompacted K/V and show only the evicted tokens (keep bit clear in bword) among the n_recent - 1 tokens just
   // before the query: the kept ones are already among the compacted rows (Table 6 of the appendix, recent-token settings).
-  auto tile = [&](const uint16_t *src_k, const uint16_t *src_v, int r0, int r_end, bool band, uint64_t bword) {
+  // In a band tile a weight of exactly 0 still meets the masked row's values in O^T += V^T . P^T, and 0 x NaN is
+  // NaN: a value row with a NaN or an infinity in it is therefore staged as zeros and noted in nf_rows[bi]; a query
+  // that does see such a row gets NaN as its whole output row, and no other query is touched by it.
+  auto tile = [&](const uint16_t *src_k, const uint16_t *src_v, int r0, int r_end, bool band, uint64_t bword, int bi) {
     __syncthreads();  // previous tile fully consumed
     // ---- stage K tile (row-major) and V tile (transposed) in LDS ----
     constexpr int CPR = D / 8;  // 16-byte chunks per row
@@ -124,6 +144,17 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
       if (r0 + r < r_end) {
         kk = *reinterpret_cast<const uint4 *>(src_k + (size_t)(r0 + r) * D + sg * 8);
         vv = *reinterpret_cast<const uint4 *>(src_v + (size_t)(r0 + r) * D + sg * 8);
+      }
+      if (band) {  // (workgroup-uniform branch; the CPR lanes of a row are neighbours inside one wave)
+        const uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
+        bool bad = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bad |= (vw[e] & 0x7f80u) == 0x7f80u || (vw[e] & 0x7f800000u) == 0x7f800000u;
+        const uint64_t row_lanes = ((1ull << CPR) - 1ull) << ((lane / CPR) * CPR);
+        if (__ballot(bad) & row_lanes) {
+          vv = make_uint4(0, 0, 0, 0);
+          if (sg == 0) atomicOr(&nf_rows[bi][r >> 5], 1u << (r & 31));
+        }
       }
       *reinterpret_cast<uint4 *>(&Ks[r * KSTR + sg * 8]) = kk;
       const uint32_t va[4] = {vv.x, vv.y, vv.z, vv.w};
@@ -162,6 +193,13 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
           const bool in_window = (unsigned)(dl - c) < (unsigned)(n_recent - 1);  // query - n_recent < key < query
           if (!in_window || ((wsub >> c) & 1u)) acc_s[sub][r] = -INFINITY;
         }
+      }
+      // does this query see, through its window, a row that was scrubbed?
+      const int lo = max(0, jq - (n_recent - 1) - r0), hi = min(kBN - 1, jq - 1 - r0);
+      if (hi >= lo) {
+        const uint64_t win = (hi - lo == 63 ? ~0ull : ((1ull << (hi - lo + 1)) - 1ull)) << lo;
+        const uint64_t nf = ((uint64_t)nf_rows[bi][1] << 32) | nf_rows[bi][0];
+        poisoned |= (win & ~bword & nf) != 0ull;
       }
     } else if (r0 + kBN > cnt_wave_lo) {  // tile crosses some query's boundary: mask keys >= cnt_q
 #pragma unroll
@@ -217,13 +255,14 @@ __global__ __launch_bounds__(256) void ag_prefill_mfma_kernel(
                                                               __builtin_bit_cast(bf16x8, pf[sub][sl]), acc_o[dt], 0, 0, 0);
         }
   };
-  for (int c0 = 0; c0 < cnt_blk; c0 += kBN) tile(Kc, Vc, c0, len_u, false, 0);
+  for (int c0 = 0; c0 < cnt_blk; c0 += kBN) tile(Kc, Vc, c0, len_u, false, 0, 0);
   if (n_recent > 1) {  // workgroup-uniform: band tiles that can hold a key of one of the workgroup's queries
     const int jb = min(qtile * BM + BM - 1, L - 1);
     const int klo = max(0, qtile * BM - (n_recent - 1)), khi = jb - 1;
-    for (int bt = klo >> 6; bt <= (khi >> 6) && khi >= klo; ++bt)
-      tile(k + (size_t)u * L * D, v + (size_t)u * L * D, bt * kBN, L, true, wu[bt]);
+    for (int bt = klo >> 6; bt <= (khi >> 6) && khi >= klo; ++bt)  // at most 3 tiles: n_recent <= 64, BM <= 128
+      tile(k + (size_t)u * L * D, v + (size_t)u * L * D, bt * kBN, L, true, in_cache_bits(wu, bo, bt, len_u), bt - (klo >> 6));
   }
+  if (poisoned) l_run = __builtin_nanf("");
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (j0 + col < L) {
@@ -265,8 +304,8 @@ __global__ __launch_bounds__(256) void ag_prefill_f32_kernel(const float *__rest
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  const int cnt = (int)min((int64_t)cnt_at(words + (size_t)u * nw, blk_off + (size_t)u * (nw + 1), j),
-                           row_off[u + 1] - row_off[u]);
+  const int64_t cap_u = row_off[u + 1] - row_off[u];  // kept tokens beyond it found no room in the cache
+  const int cnt = (int)min((int64_t)cnt_at(words + (size_t)u * nw, blk_off + (size_t)u * (nw + 1), j), cap_u);
   const float *Kc = kc + (size_t)row_off[u] * D;
   const float *Vc = vc + (size_t)row_off[u] * D;
   const float *kself = k + ((size_t)u * L + j) * D;
@@ -282,7 +321,9 @@ __global__ __launch_bounds__(256) void ag_prefill_f32_kernel(const float *__rest
   // kept ones are among the cache rows already.  Wave-uniform loop, one key at a time.
   for (int i = 1; i < n_recent && j - i >= 0; ++i) {
     const int t = j - i;
-    if ((words[(size_t)u * nw + (t >> 6)] >> (t & 63)) & 1ull) continue;
+    if (((words[(size_t)u * nw + (t >> 6)] >> (t & 63)) & 1ull) &&
+        cnt_at(words + (size_t)u * nw, blk_off + (size_t)u * (nw + 1), t) < cap_u)
+      continue;  // a cache row already
     const float *kr = k + ((size_t)u * L + t) * D, *vr = v + ((size_t)u * L + t) * D;
     float s = 0.f;
     for (int d = 0; d < D; ++d) s = fmaf(qs[wave][d], kr[d], s);

@@ -39,20 +39,6 @@
 
 #include "ag_internal.h"
 
-#ifdef AG_PREFILL_TRACE  // debug build only: per-workgroup start/end times and placement
-__device__ unsigned long long ag_dbg[8192 * 8];
-extern "C" void ag_dbg_read(unsigned long long *h) { (void)hipMemcpyFromSymbol(h, HIP_SYMBOL(ag_dbg), sizeof(ag_dbg)); }
-#define AG_TRACE_BEGIN const unsigned long long trace_t0 = wall_clock64();
-#define AG_TRACE_END(steps, empty)                                                    \
-  if (threadIdx.x == 0 && blockIdx.x < 8192) {                                        \
-    unsigned long long *d = ag_dbg + blockIdx.x * 8;                                  \
-    d[0] = trace_t0; d[1] = wall_clock64(); d[2] = __builtin_amdgcn_s_getreg(63492);  \
-    d[3] = __builtin_amdgcn_s_getreg(63508); d[4] = (steps); d[5] = (empty);          \
-  }
-#else
-#define AG_TRACE_BEGIN
-#define AG_TRACE_END(steps, empty)
-#endif
 
 namespace {
 
@@ -116,8 +102,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   constexpr int KS = D / 16;   // k-steps of S^T
   constexpr int DT = D / 32;   // 32-row tiles of O^T
   __shared__ __attribute__((aligned(1024))) uint8_t smem[kGroupB];  // [K0][K1][V0][V1], each [row][256 B]
+  // BAND: per band tile, the rows whose value row held a NaN or an infinity (see scrub_band_v below)
+  __shared__ uint32_t nf_rows[BAND ? 3 : 1][2];
 
-  AG_TRACE_BEGIN
   const int G = Hq / Hkv;
   const int HB = G / GB;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -185,17 +172,16 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   // uncompacted tensors.  bnd = number of compacted rows query j sees.
   auto in_cache = [&](uint64_t w, int pre, int j) { return ((w >> (j & 63)) & 1ull) != 0 && cnt_in(w, pre, j) < len_u; };
   auto bnd_in = [&](uint64_t w, int pre, int j) { return cnt_in(w, pre, j) + (in_cache(w, pre, j) ? 1 : 0); };
-  const int cnt_q = bnd_in(word_w, pre_w, jq);
+  // (all boundaries are clamped to the rows the cache holds: after a capacity overflow the rows that did not fit
+  // are simply not there -- their tokens count as evicted -- and nothing past len_u is attended)
+  const int cnt_q = min(bnd_in(word_w, pre_w, jq), len_u);
   const bool own_kv = chunk == 0 && !in_cache(word_w, pre_w, jq);  // this query's diagonal term comes from k, v
-  const int cnt_wave_lo = bnd_in(word_w, pre_w, min(j0, L - 1));
-  const int cnt_wave_hi = j0 < L ? bnd_in(word_w, pre_w, min(j0 + 31, L - 1)) : 0;
+  const int cnt_wave_lo = min(bnd_in(word_w, pre_w, min(j0, L - 1)), len_u);
+  const int cnt_wave_hi = j0 < L ? min(bnd_in(word_w, pre_w, min(j0 + 31, L - 1)), len_u) : 0;
   const int cnt_blk = min(bnd_in(word_b, pre_b, jb), len_u);
   const int n_tiles = (cnt_blk + kBN - 1) / kBN;       // key tiles of the item
   const int tile0 = chunk > 0 ? chunk * chunk_tiles : 0;  // this workgroup's chunk: tiles [tile0, tile0 + n_steps)
-  if (chunk > 0 && tile0 >= n_tiles) {                 // empty chunk (the whole workgroup leaves)
-    AG_TRACE_END(0, 1)
-    return;
-  }
+  if (chunk > 0 && tile0 >= n_tiles) return;           // empty chunk (the whole workgroup leaves)
   const int n_chunks = max(1, (n_tiles + chunk_tiles - 1) / chunk_tiles);
   // band tiles (chunk 0 only): 64-aligned tiles of original token positions that can hold a key of this
   // workgroup's queries, i.e. positions [first query - (n_recent - 1), last query - 1]
@@ -206,13 +192,23 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     if (khi >= klo) {
       band_t0 = klo >> 6;
       n_band = (khi >> 6) - band_t0 + 1;  // <= 3 because n_recent <= 64 and BM <= 128
-      bw0 = wu[band_t0];
-      if (n_band > 1) bw1 = wu[band_t0 + 1];
-      if (n_band > 2) bw2 = wu[band_t0 + 2];
+      // keep bits of the tokens that are among the compacted rows: all kept ones, unless the cache overflowed --
+      // a kept token that found no room is not there, so the band must show it like an evicted one
+      auto in_cache_bits = [&](int t) {
+        uint64_t w = wu[t];
+        const int room = len_u - bo[t];
+        if (room <= 0) return (uint64_t)0;
+        while (__popcll(w) > room) w &= ~(1ull << (63 - __clzll(w)));  // (never entered without an overflow)
+        return w;
+      };
+      bw0 = in_cache_bits(band_t0);
+      if (n_band > 1) bw1 = in_cache_bits(band_t0 + 1);
+      if (n_band > 2) bw2 = in_cache_bits(band_t0 + 2);
     }
   }
   // steps of this workgroup: the band tiles first, then its chunk of compacted tiles
   const int n_steps = n_band + max(0, min(n_tiles - tile0, chunk_tiles));
+  if (BAND && tid < 6) nf_rows[tid >> 1][tid & 1] = 0u;  // ordered before its first use by the barrier ahead of step 0
 
   const uint16_t *Kc = kc + (size_t)ro0 * D;
   const uint16_t *Vc = vc + (size_t)ro0 * D;
@@ -524,11 +520,46 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
     }
   };
+  // Band tiles hold rows this workgroup's queries must not see (kept tokens, tokens outside a query's window) next
+  // to rows they do see.  Their scores are replaced by -inf by a select, so K may hold anything there; but in
+  // O^T += V^T . P^T a weight of exactly 0 still meets the masked row's values, and 0 x NaN is NaN.  So every wave
+  // scrubs the value rows it loaded itself before the tile is published: a row with a NaN or an infinity in it is
+  // zeroed in LDS and noted in nf_rows; a query that does see such a row (its window mask meets nf_rows) gets NaN
+  // as its whole output row -- what the planted value would have given it -- and nobody else is touched.
+  bool poisoned = false;
+  auto scrub_band_v = [&](int i) {
+    AG_LDS uint8_t *vt = (AG_LDS uint8_t *)smem + 2 * kTileB + (i & 1) * kTileB + w4 * RPW * kRowB + lane * 16;
+#pragma unroll
+    for (int ii = 0; ii < LI; ++ii) {
+      const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(vt + ii * 4 * kRowB);
+      bool bad = false;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        bad |= (x[e] & 0x7f80u) == 0x7f80u || (x[e] & 0x7f800000u) == 0x7f800000u;
+      const uint32_t row_bad = (uint32_t)(__ballot(bad) >> (16 * ld_r)) & 0xffffu;  // the 16 lanes of my row
+      if (row_bad) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<AG_LDS u32x4 *>(vt + ii * 4 * kRowB) = z;
+        const int r = RPW * w4 + 4 * ii + ld_r;
+        if ((lane & 15) == 0) atomicOr(&nf_rows[i][r >> 5], 1u << (r & 31));
+      }
+    }
+  };
+  // keys of band tile i (bit kk = position 64 (band_t0 + i) + kk) that query jq sees through its window
+  auto band_visible = [&](int i) -> uint64_t {
+    const int r0 = (band_t0 + i) * kBN;
+    const uint64_t bword = i == 0 ? bw0 : (i == 1 ? bw1 : bw2);
+    const int lo = max(0, jq - (n_recent - 1) - r0), hi = min(kBN - 1, jq - 1 - r0);
+    if (hi < lo) return 0ull;
+    const uint64_t win = (hi - lo == 63 ? ~0ull : ((1ull << (hi - lo + 1)) - 1ull)) << lo;
+    return win & ~bword;
+  };
   // One pipeline step.  cur holds S^T of this group's tile of step i; nxt receives that of step i + 1.
   // At the top (after the barrier) K(i+1) and V(i) are resident; the step then requests K(i+2) into the K
   // buffer that step i used and V(i+1) into the V buffer of step i-1.
   auto step = [&](int i, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of K(i+1), V(i) has landed
+    if (BAND && i < n_band) scrub_band_v(i);
     __syncthreads();                                  // ... and everyone's; step i-1 is fully consumed
     if (i + 2 < n_steps) issue_k(i + 2);
     if (i + 1 < n_steps) issue_v(i + 1);
@@ -536,7 +567,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     const bool vis_cur = vis(i);                                                 // wave-uniform
     const bool vis_nxt = i + 1 < n_steps && vis(i + 1);                          // wave-uniform
     if (vis_cur) {
-      if (BAND && i < n_band) band_mask(i, cur); else mask_tile(c0, cur);
+      if (BAND && i < n_band) {
+        band_mask(i, cur);
+        const uint64_t nf = ((uint64_t)nf_rows[i][1] << 32) | nf_rows[i][0];
+        poisoned |= (band_visible(i) & nf) != 0ull;
+      } else {
+        mask_tile(c0, cur);
+      }
     }
     if (BAND && vis_nxt && !vis_cur) {
       s_tile(i + 1, nxt);   // band tiles are not all visible to a wave: the next tile may be the first it sees
@@ -567,7 +604,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     if (i + 1 < n_steps) step(i + 1, acc_b, acc_a);
   }
 
-  AG_TRACE_END(n_steps, 0)
+  if (BAND && poisoned) l_run = __builtin_nanf("");  // survives the merge of chunk states and the final division
   // ---- an item cut into chunks: store this chunk's state; the chunk that arrives last merges and writes ----
   if (n_chunks > 1) {
     const size_t item = (size_t)qtile * n_hy + hy;

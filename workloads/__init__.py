@@ -303,10 +303,10 @@ def config5_decode_lens(layer: int, B: int = 16, L: int = 2048, n_layers: int = 
     return lens.astype(np.int32).reshape(B * H)
 
 
-def config3(B: int = 32, steps: int = 256, max_len: int = 4096) -> DecodeWorkload:
+def config3(B: int = 32, steps: int = 256, max_len: int = 4096, fill_slack: Optional[float] = None) -> DecodeWorkload:
     """Decode-heavy batch: 32 heads x 128, len ~ round(max_len * U[0.1, 1]), 5 % of units len 1."""
     H, D = 32, 128
     g = rng(3, 20)
     len0 = np.rint(max_len * (0.1 + 0.9 * g.random(B * H))).astype(np.int32)
     len0[g.random(B * H) < 0.05] = 1
-    return decode_batch(3, "cfg3_decode_B%d" % B, "bf16", B, H, H, D, len0, steps, pos0=max_len)
+    return decode_batch(3, "cfg3_decode_B%d" % B, "bf16", B, H, H, D, len0, steps, pos0=max_len, fill_slack=fill_slack)
