@@ -121,11 +121,17 @@ def prefill_leg(args, torch, ag, W):
     for _ in range(2):
         run()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    block_s = []
+    for _ in range(max(1, args.repeats)):       # the timed block, repeated: spread of one block of --steps steps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        block_s.append(t1 - t0)
+    block_s.sort()
+    t0, t1 = 0.0, block_s[len(block_s) // 2]    # the median block is the one reported
     # per-kernel durations: HIP event pairs around every kernel, same steps launched eagerly
     ctx.timing_enable(True)
     torch.cuda.synchronize()
@@ -147,6 +153,8 @@ def prefill_leg(args, torch, ag, W):
     ach = flops / (pf_ms * 1e-3) / 1e12
     res = {
         "seconds": t1 - t0,
+        "ms_per_step_spread": {"min": block_s[0] / args.steps * 1e3, "median": block_s[len(block_s) // 2] / args.steps * 1e3,
+                               "max": block_s[-1] / args.steps * 1e3, "blocks": len(block_s)},
         "seconds_instrumented": t3 - t2,
         "tokens": B * L * args.steps,
         "kernel_ms": per_kernel,
@@ -168,6 +176,12 @@ def prefill_leg(args, torch, ag, W):
 
 
 def decode_leg(args, torch, ag, W):
+    """Config 3: `--decode-steps` decode steps (256) over B = 32 x 32 ragged caches, Bernoulli(0.5) appends.
+    Three passes from the same starting lengths: (1) eager launches, no instrumentation: wall clock; (2) the same
+    steps captured once into ONE HIP graph (every step's position and inputs are baked into its nodes) and replayed:
+    wall clock -- the graph's result is first checked against the eager pass bit for bit; (3) eager with the library's
+    per-launch events: kernel durations.  The headline of the leg is the whole step (both kernels and the gaps
+    between them) of the faster of (1) and (2); the streaming kernel alone is reported beside it."""
     steps, warm = args.decode_steps, min(args.warmup, 8)
     wl = W.config3(B=args.decode_batch, steps=steps + warm)
     B, Hq, Hkv, D = wl.B, wl.Hq, wl.Hkv, wl.D
@@ -187,33 +201,86 @@ def decode_leg(args, torch, ag, W):
         q, kn, vn, nf = ins[s % n_in]
         ag.ag_decode_attn(ctx, q, kn, vn, nf, wl.pos0 + s, wl.scale, cache, out)
 
+    def all_steps():
+        for s in range(warm, warm + steps):
+            step(s)
+
     for s in range(warm):
         step(s)
     torch.cuda.synchronize()
-    len_before = cache.len.cpu().numpy().astype(np.int64)
+    len_start = cache.len.clone()
+    len_before = len_start.cpu().numpy().astype(np.int64)
+
+    def timed(run, repeats):
+        """wall-clock seconds of `run` (all the steps) from len_start, `repeats` times"""
+        secs = []
+        for _ in range(repeats):
+            cache.len.copy_(len_start)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run()
+            torch.cuda.synchronize()
+            secs.append(time.perf_counter() - t0)
+        return secs
+
+    eager_s = timed(all_steps, args.repeats)
+    ref_out, ref_len = out.clone(), cache.len.clone()
+    len_after = ref_len.cpu().numpy().astype(np.int64)
+    # one graph that holds all the steps; replays checked against the eager pass, with eager work in between
+    graph_s = None
+    if not args.no_decode_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        cache.len.copy_(len_start)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            all_steps()
+        torch.cuda.current_stream().wait_stream(side)
+        for r in range(2):
+            cache.len.copy_(len_start)
+            out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            if not (torch.equal(out, ref_out) and torch.equal(cache.len, ref_len)):
+                raise RuntimeError("decode graph replay %d differs from the eager steps" % r)
+            cache.len.copy_(len_start)
+            for s in range(warm, warm + 4):     # eager work between replays
+                step(s)
+            torch.cuda.synchronize()
+        graph_s = timed(graph.replay, args.repeats)
+    # kernel durations: the library's events on each launch
+    cache.len.copy_(len_start)
     ctx.timing_enable(True)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(warm, warm + steps):
-        step(s)
+    all_steps()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
     times = ctx.timing_read()
     ctx.timing_enable(False)
     ctx.poll_error()
-    len_after = cache.len.cpu().numpy().astype(np.int64)
     # rows read per step grow by the appends; appends are spread evenly, so use the mean of first and last
     rows_per_step = 0.5 * (len_before.sum() + len_after.sum())
     bytes_per_step = rows_per_step * D * 2 * 2
     part_ms = times["decode_partial"][0] / max(times["decode_partial"][1], 1)
     merge_ms = times["decode_merge"][0] / max(times["decode_merge"][1], 1)
     ach = bytes_per_step / (part_ms * 1e-3) / 1e9
+    best = min(eager_s + (graph_s or []))
+    use_graph = graph_s is not None and min(graph_s) <= min(eager_s)
+    med = lambda xs: sorted(xs)[len(xs) // 2]
+    step_ms = best / steps * 1e3
     res = {
-        "metric": "decode attention HBM GB/s", "value": bytes_per_step * steps / (t1 - t0) / 1e9, "unit": "GB/s",
-        "steps": steps, "ms_per_step": (t1 - t0) / steps * 1e3,
+        "metric": "decode attention HBM GB/s, whole step (both kernels, gaps included)",
+        "value": bytes_per_step / (step_ms * 1e-3) / 1e9, "unit": "GB/s",
+        "steps": steps, "ms_per_step": step_ms, "launch": "one hip graph of all steps" if use_graph else "eager",
+        "ms_per_step_eager": {"min": min(eager_s) / steps * 1e3, "median": med(eager_s) / steps * 1e3,
+                              "max": max(eager_s) / steps * 1e3},
+        "ms_per_step_graph": None if graph_s is None else {"min": min(graph_s) / steps * 1e3,
+                                                           "median": med(graph_s) / steps * 1e3,
+                                                           "max": max(graph_s) / steps * 1e3},
         "kernel_ms": {"decode_partial": part_ms, "decode_merge": merge_ms},
         "roofline": {"kernel": "ag_decode_partial_kernel<bf16,128,1>", "bound": "hbm", "achieved": ach,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "frac_step": bytes_per_step / (step_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": TRAFFIC_BYTES.get(("decode", B, steps)),
                      "bytes_per_launch": bytes_per_step, "avg_launch_ms": part_ms},
         "config": {"workload": wl.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D,
@@ -592,6 +659,10 @@ def main():
                     help="also time config 5's decode phase (one token through 32 layers, eager and from a HIP graph)")
     ap.add_argument("--stack-steps", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching it eagerly")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="times the timed block of --steps steps (and the decode leg's block) is repeated; the line "
+                         "carries min / median / max, `value` is the median")
+    ap.add_argument("--no-decode-graph", action="store_true", help="decode leg: eager launches only")
     ap.add_argument("--skip-decode", action="store_true")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-overlap", action="store_true", help="skip the multi-layer gate-overlap measurement")
@@ -646,6 +717,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": pre["seconds"] / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": pre["config"], "kernel_ms": pre["kernel_ms"],
+        "ms_per_step_spread": pre["ms_per_step_spread"],
         "ms_per_step_with_kernel_events": pre["seconds_instrumented"] / args.steps * 1e3, "roofline": pre["roofline"],
         "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
         "next_layer_gate_overlap": overlap, "decode_stack": stack, "kv_projection": proj, "norm_gate": norm_gate, "prefill_power": power, "machine": machine,

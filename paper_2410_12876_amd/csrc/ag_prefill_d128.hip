@@ -56,7 +56,7 @@ constexpr int kBN = 64;                   // keys per tile
 constexpr int kRowB = D * 2;              // bytes per cache row
 constexpr int kTileB = kBN * kRowB;       // 16 KiB per K or V tile
 constexpr int kGroupB = 4 * kTileB;       // LDS per group: [K0][K1][V0][V1]
-constexpr float kRescaleGap = 8.f;        // log2 units the maximum may lag before O is rescaled
+constexpr float kLazyLimit = 1073741824.f; // 2^30: a lane's sum of weights above this raises its reference maximum
 constexpr float kEmptyMax = -1.0e30f;     // "no key seen yet" reference maximum (finite on purpose)
 
 // swizzle of the 16-byte chunk index of LDS row r: swap the two low bit pairs of r
@@ -423,36 +423,56 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   uint4 pf[2][2];  // P fragments (B operand of O^T), [sub][16-key slab]
   float alpha_pending = 1.f;
   bool any_raise = false;
-  // softmax of one tile held in acc (key = c0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col) -> pf, l_run, m_run
-  auto softmax_tile = [&](f32x16 (&acc)[2]) {
+  // Softmax of one tile held in acc (key = c0 + 32 sub + 8 (r/4) + 4 hb + r%4, query = col) -> pf, l_run, m_run.
+  // The matrix pipe and the vector ALU share the wave's issue slots, so every vector instruction per element counts;
+  // the common case is therefore three per element and a half: one fused multiply-add (scale, minus the reference
+  // maximum), one exponential, half a pack, half a dot2 that sums the PACKED pair -- the row sum is then the sum of
+  // exactly the bf16 weights the second MFMA multiplies with.  No maximum is taken there: the exponentials are formed
+  // against the reference maximum as it stands, and only if a lane's sum of weights then exceeds 2^kLazyLog2 (or is
+  // not a number: the first tile, whose reference is still "nothing seen") does the wave take the slow branch, which
+  // finds the row maxima, raises the references that need it and forms the weights again.  A stale reference is
+  // exact after the final division by the row sum -- floating point is indifferent to the common factor -- and
+  // 2^kLazyLog2 times the 64 keys of a tile times the tiles of the longest prompt stays far inside fp32's range.
+  // A lane raises its own reference only (its pair lane^32 decides with it), so a query never depends on the
+  // queries that share its wave.
+  float psum;
+  auto weights = [&](f32x16 (&acc)[2]) {
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+    psum = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      float p[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(fmaf(acc[sub][r], qscale, -m_run));
+#pragma unroll
+      for (int sl = 0; sl < 2; ++sl) {
+        pf[sub][sl] = make_uint4(pack2(p[8 * sl + 0], p[8 * sl + 1]), pack2(p[8 * sl + 2], p[8 * sl + 3]),
+                                 pack2(p[8 * sl + 4], p[8 * sl + 5]), pack2(p[8 * sl + 6], p[8 * sl + 7]));
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf[sub][sl].x), ones, psum, false);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf[sub][sl].y), ones, psum, false);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf[sub][sl].z), ones, psum, false);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf[sub][sl].w), ones, psum, false);
+      }
+    }
+  };
+  auto softmax_tile = [&](f32x16 (&acc)[2]) {  // the common case; sets any_raise when softmax_raise must follow
+    weights(acc);
+    alpha_pending = 1.f;
+    any_raise = __any(!(psum <= kLazyLimit));
+  };
+  auto softmax_raise = [&](f32x16 (&acc)[2]) {  // rare: some row of the wave outgrew its reference maximum
+    const uint64_t big = __ballot(!(psum <= kLazyLimit));
+    const bool mine = (((big | (big >> 32) | (big << 32)) >> lane) & 1ull) != 0;  // this lane's query, either half
     float mx = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[sub][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * qscale;
-    // The reference maximum is raised only when a row exceeds it by more than 2^kRescaleGap; each lane uses
-    // its own factor (1 when it has no need), so a query never depends on the queries sharing its wave.
-    const bool raise = mx > m_run + kRescaleGap;
-    const float m_new = raise ? mx : m_run;
-    alpha_pending = __builtin_amdgcn_exp2f(m_run - m_new);
-    any_raise = __any(raise);
+    const float m_new = mine && mx > m_run ? mx : m_run;   // (selects: the others keep their reference and factor 1)
+    alpha_pending = mine && mx > m_run ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
     m_run = m_new;
-    float psum = 0.f;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      float p[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(fmaf(acc[sub][r], qscale, -m_run));
-        psum += p[r];
-      }
-#pragma unroll
-      for (int sl = 0; sl < 2; ++sl)
-        pf[sub][sl] = make_uint4(pack2(p[8 * sl + 0], p[8 * sl + 1]), pack2(p[8 * sl + 2], p[8 * sl + 3]),
-                                 pack2(p[8 * sl + 4], p[8 * sl + 5]), pack2(p[8 * sl + 6], p[8 * sl + 7]));
-    }
-    l_run = l_run * alpha_pending + psum;
+    weights(acc);
   };
   auto mask_tile = [&](int c0, f32x16 (&acc)[2]) {
     if (c0 + kBN > cnt_wave_lo) {  // the tile crosses some query's boundary: mask keys >= cnt_q
@@ -586,12 +606,17 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       for (int n = 0; n < 16; ++n) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         if (n < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
       }
+      if (any_raise) softmax_raise(cur);
     } else if (vis_cur) {
       softmax_tile(cur);
+      if (any_raise) softmax_raise(cur);
     }
-    if (vis_cur) pv_tile(i);
+    if (vis_cur) {
+      l_run = l_run * alpha_pending + psum;
+      pv_tile(i);
+    }
   };
   f32x16 acc_a[2], acc_b[2];
   if (n_steps > 0) {
