@@ -285,7 +285,7 @@ __global__ __launch_bounds__(64 * kFusedWaves, PF == 2 ? 2 : 1) void ag_gate_fus
 // RMS normalisation fused with the gate: x = h / sqrt(mean_c h^2 + eps) * g, rounded once to bf16, written out for
 // the projections that follow, and multiplied by W from the same registers, so the gate costs no second read of x.
 // One workgroup of 8 waves per 32 tokens.  Wave w owns the 64-feature chunks w, w + 8, ... (at most NCH of
-// them: d_in <= 4096) of all 32 rows and keeps them in registers for the whole kernel, so all loads of the tile are
+// them: d_in <= 4096 with 32-token tiles, <= 8192 with 16-token tiles) of all rows of the tile and keeps them in registers for the whole kernel, so all loads of the tile are
 // in flight at once.  A chunk is one 128-byte line per row; a load or store instruction moves 8 whole lines (lane
 // -> row 8 i + lane / 8, 16-byte piece lane % 8).  The squares are summed per lane, over the 8 lanes of a row and
 // then over the waves through LDS in wave order.  After the scaling the chunk is stored from the same registers

@@ -6,8 +6,9 @@
 #include <stdio.h>
 
 #include "ag.h"
+#include "ag_bench.h"
 
-// Kernels that ag_timing_* can time (ids are part of the ABI, see ag.h).
+// Kernels that ag_timing_* can time (ids are part of the ABI, see ag_bench.h).
 enum { AG_K_GATE = 0, AG_K_GATE_FINALIZE, AG_K_FLAG_SCAN, AG_K_COMPACT, AG_K_PREFILL, AG_K_DECODE_PARTIAL,
        AG_K_DECODE_MERGE, AG_K_MHA_PROJ, AG_K_MHA_ATTN, AG_K_NORM_GATE, AG_K_COUNT };
 constexpr int kTimerSlots = 1024;  // launches remembered per kernel id
@@ -138,7 +139,7 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
                                   const ag_pf_plan &plan, float *part, bool out_token_major = false,
                                   ag_evpair ev = ag_evpair{nullptr, nullptr});
 
-// RMS normalisation of h (weights g, bf16, d_in <= 4096) fused with the gate; x_out may be h itself.
+// RMS normalisation of h (weights g, bf16, d_in <= 8192) fused with the gate; x_out may be h itself.
 hipError_t ag_launch_norm_gate(ag_ctx *ctx, hipStream_t s, const void *h, int B, int L, int d_in, const void *g,
                                float eps, const void *w, const float *bias, int H_f, float thr, int n_sink,
                                void *x_out, float *logits, uint8_t *flags, ws_cursor &ws);

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include "ag.h"
+#include "ag_bench.h"
 
 int main(void) {
   ag_ctx *ctx = NULL;

@@ -527,3 +527,27 @@ def test_rmsnorm_gate_is_the_gate_of_the_stored_x():
         assert np.array_equal(logits[0, :, j], x[0, :, c])
     l2, f2 = oracle.gate(x, w, np.zeros(4, np.float32), 0.5, 0)
     assert np.array_equal(l2, logits) and np.array_equal(f2, flags)
+
+
+# ------------------------------------------------------------------ memory safety of the checker itself
+def test_oracle_runs_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """oracle/ag_oracle.c compiled together with tests/oracle_sanitized.c by gcc with
+    -fsanitize=address,undefined (host code; statically linked runtime) and run on edge shapes: L = 1, a prompt
+    shorter than the recent window, GQA, empty and full units, caches with no room and with exactly enough.  Any
+    out-of-bounds access, overflow or leak in the oracle aborts the run."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "oracle_sanitized")
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-static-libasan", "-Wall", "-Wextra", "-Werror", "-o", exe, os.path.join(root, "tests", "oracle_sanitized.c"),
+           os.path.join(root, "oracle", "ag_oracle.c"), "-lm"]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=180)
+    if r.returncode != 0 and ("cannot find" in r.stderr or "libasan" in r.stderr):
+        pytest.skip("sanitizer runtime not installed: " + r.stderr[-200:])
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=180,
+                       env=dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", OMP_NUM_THREADS="4"))
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr[-3000:]

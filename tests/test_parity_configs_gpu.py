@@ -929,3 +929,47 @@ def test_config2_full_size_step_as_the_benchmark_runs_it():
     print("cfg2 step: %d of %d logits within 1e-3 of the threshold, %d flags differ there" %
           (int(near.sum()), near.size, int((got_flags != ref_flags).sum())))
     ctx.close()
+
+
+# ------------------------------------------------------------------------- the 64-queries-per-wave variant (experiment)
+_Q64_CHILD = r"""
+import math, sys
+import numpy as np
+sys.path.insert(0, %(tests)r); sys.path.insert(0, %(root)r)
+import oracle, workloads as W
+from test_parity_configs_gpu import _prefill_case, check_sampled_rows, sample_rows
+from gpu_util import ensure_built, host_f32
+ensure_built()
+for name, B, Hq, Hkv, L in (("split, balanced order", 1, 16, 16, 2048), ("GQA, four heads per workgroup", 1, 8, 2, 1500),
+                            ("two heads per workgroup, ragged", 2, 4, 2, 333), ("few heads, 4 chunks", 1, 3, 3, 4096),
+                            ("many heads, head-major order", 4, 32, 32, 512)):
+    g = np.random.default_rng(170)
+    flags = (g.random((B, Hkv, L)) < np.linspace(1.0, 0.05, Hkv)[None, :, None]).astype(np.uint8)
+    flags[:, 0] = 1
+    flags[:, -1] = 0
+    q, k, v, out = _prefill_case(B, Hq, Hkv, L, flags, 171)
+    got = host_f32(out)
+    if L <= 1500:
+        ref = oracle.prefill_attn(q.f32, k.f32, v.f32, flags, 1.0 / math.sqrt(128))
+        check_sampled_rows(got, q, k, v, flags, 1.0 / math.sqrt(128), np.arange(L, dtype=np.int32), name)
+    else:
+        check_sampled_rows(got, q, k, v, flags, 1.0 / math.sqrt(128), sample_rows(L, 172, 6), name)
+    G = Hq // Hkv
+    assert np.array_equal(got[:, -G:], np.repeat(v.f32[:, -1:], G, axis=1))      # fully evicted head: out == v
+print("q64 ok")
+"""
+
+
+def test_prefill_64_queries_per_wave_variant_matches_the_oracle():
+    """The experimental prefill kernel with 64 queries per wave (environment AG_PREFILL_Q64=1, read once per process,
+    hence the child process): same plan, split and merge as the 4-wave kernel, checked against the oracle on launch
+    shapes that cover one, two and four query heads per workgroup, the key-chunk split and the head-major order."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    env = dict(os.environ, AG_PREFILL_Q64="1")
+    r = subprocess.run([sys.executable, "-c", _Q64_CHILD % {"tests": here, "root": os.path.dirname(here)}], env=env,
+                       capture_output=True, text=True, timeout=280)
+    print(r.stdout[-1500:])
+    assert r.returncode == 0 and "q64 ok" in r.stdout, r.stderr[-3000:]
