@@ -143,10 +143,28 @@ ag_status ag_gate_mha(ag_ctx *ctx, void *hip_stream, const void *x, ag_dtype dty
                       float tau, int n_sink, float *logits_out, uint8_t *flags_out);
 
 /*
+ * Packed cache layout (Sec. 3.3: only the retained k, v take cache memory -- the saving that Sec. 4.2.3 and Fig. 3
+ * report).  Computes, on the device and from the flags alone, slab offsets that give every unit exactly its
+ * retained rows plus `room` spare rows for the tokens appended while decoding:
+ *   row_off[0] = 0,   row_off[u + 1] = min(row_off[u] + kept(u) + room, total_rows),   kept(u) = #{t : flags[u,t] != 0}
+ * so a cache of sum_u kept(u) + B * Hkv * room rows holds the prompt instead of B * Hkv * (L + room).  Call it before
+ * ag_compact_kv, ag_compact_prefill_attn or ag_project_compact_kv on the same flags, with cache->row_off = row_off;
+ * decoding then appends into the spare rows (a unit that has used them up drops further rows: ag_poll_error).
+ * flags uint8 [B, Hkv, L]; row_off int64 [B * Hkv + 1], written; total_rows = rows allocated in the cache's k, v, idx
+ * (host value): a layout that needs more is cut off there -- the units past the end get no rows, the compaction
+ * drops theirs and ag_poll_error reports AG_ECAPACITY.  rows_needed (device int64, may be NULL) receives the rows
+ * the layout would need, sum_u (kept(u) + room), so that a caller can size or check its allocation without
+ * synchronising here.  Needs 4 * B * Hkv bytes of workspace.
+ */
+ag_status ag_pack_row_off(ag_ctx *ctx, void *hip_stream, const uint8_t *flags, int B, int Hkv, int L, int room,
+                          int64_t total_rows, int64_t *row_off, int64_t *rows_needed);
+
+/*
  * KV-cache after prefilling (Sec. 3.3; Sec. 3.1 prefilling stage): stable stream compaction.
  * For each unit, rows t of k, v [B, Hkv, L, D] with flags[b,g,t] != 0 are copied, in increasing t, to the
  * unit's cache rows; idx gets pos0 + t and len the number of rows.  The result is unique, hence bit-exact.
- * cache->row_off must be filled by the caller; rows beyond a unit's capacity are dropped (ag_poll_error).
+ * cache->row_off holds the units' slab offsets: filled by the caller (any layout, e.g. u * capacity) or by
+ * ag_pack_row_off (packed: retained rows + room); rows beyond a unit's capacity are dropped (ag_poll_error).
  */
 ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void *v, const uint8_t *flags,
                         int L, int pos0, ag_kv_cache *cache);

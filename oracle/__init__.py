@@ -233,3 +233,20 @@ def decode_step(q, k_new, v_new, new_flags, pos: int, cache: Cache, scale: float
                                           C.c_double(scale), _p(cache.k), _p(cache.v), _p(cache.idx),
                                           _p(cache.row_off), _p(cache.len), _p(out))
     return out, int(dropped)
+
+
+def packed_row_off(flags, room: int, total_rows: int):
+    """Slab offsets of the packed cache layout (Sec. 3.3: only the retained rows take cache memory): unit u gets its
+    kept rows plus `room` spare rows, units back to back, the layout cut off at total_rows.  Plain loop over the
+    units.  Returns (row_off i64 [units + 1], rows the layout needs)."""
+    f = np.asarray(flags)
+    f = f.reshape(-1, f.shape[-1])
+    row_off = np.zeros(f.shape[0] + 1, dtype=np.int64)
+    need = 0
+    for u in range(f.shape[0]):
+        kept = 0
+        for t in range(f.shape[1]):
+            kept += 1 if f[u, t] != 0 else 0
+        need += kept + room
+        row_off[u + 1] = min(need, total_rows)
+    return row_off, need

@@ -24,7 +24,7 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
-           "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_rmsnorm_gate", "ag_compact_kv", "ag_prefill_attn", "ag_prefill_attn_recent",
+           "ag_probe_mfma", "ag_probe_copy", "ag_gate", "ag_rmsnorm_gate", "ag_compact_kv", "ag_pack_row_off", "ag_prefill_attn", "ag_prefill_attn_recent",
            "ag_compact_prefill_attn", "ag_project_compact_kv", "ag_project_compact_workspace_bytes", "ag_decode_attn", "ag_decode_attn_static", "ag_decode_static_scratch_bytes", "ag_decode_scratch_bytes", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
 
 
@@ -85,6 +85,8 @@ def load() -> C.CDLL:
     lib.ag_rmsnorm_gate.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, f32, vp, vp, i32, f32, i32, vp, vp, vp]
     lib.ag_compact_kv.restype = C.c_int
     lib.ag_compact_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.POINTER(ag_kv_cache)]
+    lib.ag_pack_row_off.restype = C.c_int
+    lib.ag_pack_row_off.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, vp, vp]
     lib.ag_prefill_attn.restype = C.c_int
     lib.ag_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32,
                                     C.POINTER(ag_kv_cache), vp]
@@ -242,6 +244,14 @@ def ag_compact_kv(ctx: Context, k, v, flags, pos0: int, cache: KVCache, stream=N
     L = k.shape[2]
     ctx._check(ctx._lib.ag_compact_kv(ctx._h, _stream_ptr(stream), _ptr(k), _ptr(v), _ptr(flags), L, pos0,
                                       C.byref(cache.c)))
+
+
+def ag_pack_row_off(ctx: Context, flags, room: int, total_rows: int, row_off, rows_needed=None, stream=None) -> None:
+    """flags u8 [B, Hkv, L] -> row_off i64 [B*Hkv + 1] of the packed layout (retained rows + room per unit, cut off at
+    total_rows); rows_needed i64 [1] (or None) receives the rows the layout needs."""
+    B, Hkv, L = flags.shape
+    ctx._check(ctx._lib.ag_pack_row_off(ctx._h, _stream_ptr(stream), _ptr(flags), B, Hkv, L, room, total_rows,
+                                        _ptr(row_off), _ptr(rows_needed)))
 
 
 def project_compact_workspace_bytes(B: int, L: int, Hkv: int) -> int:

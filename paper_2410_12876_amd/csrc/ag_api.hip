@@ -328,6 +328,24 @@ ag_status ag_compact_kv(ag_ctx *ctx, void *hip_stream, const void *k, const void
   return AG_OK;
 }
 
+ag_status ag_pack_row_off(ag_ctx *ctx, void *hip_stream, const uint8_t *flags, int B, int Hkv, int L, int room,
+                          int64_t total_rows, int64_t *row_off, int64_t *rows_needed) {
+  if (!ctx) return AG_EINVAL;
+  AG_REQUIRE(flags && row_off, AG_EINVAL, "ag_pack_row_off: null pointer");
+  AG_REQUIRE(B > 0 && Hkv > 0 && L > 0, AG_EINVAL, "ag_pack_row_off: B, Hkv, L must be positive");
+  AG_REQUIRE(room >= 0 && total_rows >= 0, AG_EINVAL, "ag_pack_row_off: room and total_rows must not be negative");
+  AG_REQUIRE(L <= kMaxL, AG_EUNSUPPORTED, "ag_pack_row_off: L = %d exceeds %d", L, kMaxL);
+  AG_REQUIRE((int64_t)B * Hkv <= 65535, AG_EUNSUPPORTED, "ag_pack_row_off: B * Hkv exceeds 65535");
+  const int units = B * Hkv;
+  ws_cursor ws = cursor(ctx);
+  int32_t *kept = ws.take<int32_t>(units);
+  AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_pack_row_off: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes, ws.off);
+  ag_status st = need_device(ctx);
+  if (st != AG_OK) return st;
+  AG_HIP(ag_launch_pack_row_off((hipStream_t)hip_stream, flags, units, L, room, total_rows, kept, row_off, rows_needed));
+  return AG_OK;
+}
+
 size_t ag_project_compact_workspace_bytes(int B, int L, int Hkv) {
   if (B <= 0 || L <= 0 || Hkv <= 0) return 0;
   return ag_ws_project_compact_bytes(B * Hkv, L);

@@ -274,7 +274,66 @@ __global__ void ag_slab_offsets_kernel(int64_t *row_off, int units, int L) {
   if (u <= units) row_off[u] = (int64_t)u * L;
 }
 
+// Packed layout, step 1: kept flags per unit.  grid = units.
+__global__ __launch_bounds__(256) void ag_count_kept_kernel(const uint8_t *__restrict__ flags, int L,
+                                                            int32_t *__restrict__ kept) {
+  __shared__ int32_t part[4];
+  const uint8_t *f = flags + (size_t)blockIdx.x * L;
+  const int tid = threadIdx.x;
+  int n = 0;
+  if ((reinterpret_cast<uintptr_t>(f) & 3) == 0) {
+    const uint32_t *f4 = reinterpret_cast<const uint32_t *>(f);
+    for (int i = tid; i < L / 4; i += 256) {
+      const uint32_t x = f4[i];
+      n += __popc((((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u);  // non-zero bytes of x
+    }
+    for (int i = (L & ~3) + tid; i < L; i += 256) n += f[i] != 0;
+  } else {
+    for (int i = tid; i < L; i += 256) n += f[i] != 0;
+  }
+  for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
+  if ((tid & 63) == 0) part[tid >> 6] = n;
+  __syncthreads();
+  if (tid == 0) kept[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
+// Packed layout, step 2 (one workgroup): row_off[u + 1] = min(sum_{u' <= u} (kept[u'] + room), total_rows).
+__global__ __launch_bounds__(256) void ag_pack_offsets_kernel(const int32_t *__restrict__ kept, int units, int room,
+                                                              int64_t total_rows, int64_t *__restrict__ row_off,
+                                                              int64_t *__restrict__ rows_needed) {
+  __shared__ int64_t wave_sum[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (units + 255) / 256;
+  const int u0 = min(units, tid * per), u1 = min(units, u0 + per);
+  int64_t sum = 0;
+  for (int u = u0; u < u1; ++u) sum += (int64_t)kept[u] + room;
+  int64_t incl = sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int64_t up = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_sum[wave] = incl;
+  __syncthreads();
+  int64_t run = incl - sum;
+  for (int w = 0; w < wave; ++w) run += wave_sum[w];
+  if (tid == 0) row_off[0] = 0;
+  for (int u = u0; u < u1; ++u) {
+    run += (int64_t)kept[u] + room;
+    row_off[u + 1] = run < total_rows ? run : total_rows;
+  }
+  if (tid == 255 && rows_needed) *rows_needed = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+}
+
 }  // namespace
+
+hipError_t ag_launch_pack_row_off(hipStream_t s, const uint8_t *flags, int units, int L, int room, int64_t total_rows,
+                                  int32_t *kept, int64_t *row_off, int64_t *rows_needed) {
+  hipLaunchKernelGGL(ag_count_kept_kernel, dim3(units), dim3(256), 0, s, flags, L, kept);
+  hipLaunchKernelGGL(ag_pack_offsets_kernel, dim3(1), dim3(256), 0, s, kept, units, room, total_rows, row_off,
+                     rows_needed);
+  return hipGetLastError();
+}
 
 hipError_t ag_launch_slab_offsets(hipStream_t s, int64_t *row_off, int units, int L) {
   hipLaunchKernelGGL(ag_slab_offsets_kernel, dim3((units + 256) / 256), dim3(256), 0, s, row_off, units, L);

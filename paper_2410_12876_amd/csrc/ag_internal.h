@@ -116,6 +116,11 @@ hipError_t ag_launch_flag_scan(ag_ctx *ctx, hipStream_t s, const uint8_t *flags,
 // row_off[u] = u * L for u in [0, units]: one full-length slab per unit.
 hipError_t ag_launch_slab_offsets(hipStream_t s, int64_t *row_off, int units, int L);
 
+// Packed cache layout: row_off[u + 1] = min(sum_{u' <= u} (kept flags of u' + room), total_rows); kept[units] is
+// scratch; rows_needed (nullable) receives the unclamped total.
+hipError_t ag_launch_pack_row_off(hipStream_t s, const uint8_t *flags, int units, int L, int room, int64_t total_rows,
+                                  int32_t *kept, int64_t *row_off, int64_t *rows_needed);
+
 // The scan above and the stable compaction of the kept K/V rows in one launch (timed as the compaction).
 hipError_t ag_launch_scan_compact(ag_ctx *ctx, hipStream_t s, const uint8_t *flags, int units, int L, uint64_t *words,
                                   int32_t *blk_off, const ag_pf_plan *plan, const void *k, const void *v, int row_bytes,

@@ -93,6 +93,10 @@ def test_error_paths_without_device(lib):
     cache = make_cache()
     expect(ag.AG_EHIP, ag.ag_compact_kv, ctx, k, k, f2, 0, cache, stream=0)
     expect(ag.AG_EINVAL, ag.ag_compact_kv, ctx, k, None, f2, 0, cache, stream=0)
+    ro = torch.zeros(3, dtype=torch.int64)
+    expect(ag.AG_EHIP, ag.ag_pack_row_off, ctx, f2, 4, 100, ro, None, stream=0)
+    expect(ag.AG_EINVAL, ag.ag_pack_row_off, ctx, f2, -1, 100, ro, None, stream=0)            # negative room
+    expect(ag.AG_EINVAL, ag.ag_pack_row_off, ctx, f2, 4, 100, None, None, stream=0)           # null row_off
     expect(ag.AG_EHIP, ag.ag_prefill_attn, ctx, q, k, k, f2, 0.125, cache, q.clone(), stream=0)
     expect(ag.AG_EHIP, ag.ag_prefill_attn, ctx, q, k, k, f2, 0.125, None, q.clone(), stream=0)
     expect(ag.AG_EINVAL, ag.ag_prefill_attn, ctx, q, k, k, f2, 0.0, cache, q.clone(), stream=0)  # scale

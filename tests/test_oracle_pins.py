@@ -551,3 +551,20 @@ def test_oracle_runs_clean_under_address_and_undefined_behaviour_sanitizers(tmp_
     r = subprocess.run([exe], capture_output=True, text=True, timeout=180,
                        env=dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", OMP_NUM_THREADS="4"))
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr[-3000:]
+
+
+def test_packed_row_off_hand_example_and_closed_form():
+    """Packed cache layout (Sec. 3.3: only retained rows take memory): worked by hand for three units, then the
+    prefix-sum closed form on random flags, with and without the cut at total_rows."""
+    flags = np.array([[1, 0, 1], [0, 0, 0], [1, 1, 1]], dtype=np.uint8)      # kept 2, 0, 3
+    ro, need = oracle.packed_row_off(flags, 2, 100)
+    assert ro.tolist() == [0, 4, 6, 11] and need == 11
+    ro, need = oracle.packed_row_off(flags, 2, 8)                              # the allocation ends inside unit 2
+    assert ro.tolist() == [0, 4, 6, 8] and need == 11
+    ro, need = oracle.packed_row_off(flags.reshape(1, 3, 3), 0, 100)           # [B, Hkv, L] input, no spare rows
+    assert ro.tolist() == [0, 2, 2, 5] and need == 5
+    g = np.random.default_rng(5)
+    f = (g.random((7, 50)) < 0.4).astype(np.uint8)
+    ro, need = oracle.packed_row_off(f, 3, 10 ** 9)
+    assert np.array_equal(ro[1:], np.cumsum(f.sum(axis=1) + 3)) and need == int(f.sum()) + 21
+    assert np.array_equal(np.diff(ro), f.sum(axis=1) + 3)

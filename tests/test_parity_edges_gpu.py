@@ -127,3 +127,97 @@ def test_prefill_after_a_cache_overflow_attends_only_the_rows_that_fit(dtype, Hq
     ref = oracle.prefill_attn(q.f32, k.f32, v.f32, fits, scale, n_recent=n_recent)
     assert np.isfinite(got).all()
     assert attn_error(dtype, got, ref) <= attn_tolerance(dtype)
+
+
+# --------------------------------------------------------------------------------------------- packed cache layout
+def test_packed_cache_layout_prefill_equals_slabs_and_decode_fills_the_spare_rows():
+    """ag_pack_row_off (Sec. 3.3: only the retained rows take cache memory) on a cfg2-like layer: offsets and the
+    needed-rows word against the oracle's plain loop, every unit's capacity = its kept rows + room, the compaction
+    into the packed cache against the oracle's, the prefill over the packed cache bit-identical to the prefill over
+    full-length slabs, then `room` decode steps that use up the spare rows exactly and one more that is dropped."""
+    B, H, L, D, room = 1, 16, 2048, 128, 3
+    g = np.random.default_rng(400)
+    q, k, v = (W.store(g.standard_normal((B, H, L, D)).astype(np.float32), "bf16") for _ in range(3))
+    flags = (g.random((B, H, L)) < np.linspace(0.9, 0.05, H)[None, :, None]).astype(np.uint8)
+    flags[0, 5] = 0                    # a fully evicted unit: capacity = room
+    scale = 1.0 / math.sqrt(D)
+    want_ro, need = oracle.packed_row_off(flags, room, 10 ** 9)
+    total = int(need)
+    assert total < B * H * (L + room) * 0.6          # the layout is much smaller than slabs
+    ctx = make_ctx(B, L, H, H, D, ag.AG_BF16, cache_rows=total)
+    dq, dk, dv, df = dev(q), dev(k), dev(v), dev(flags)
+    row_off = torch.full((B * H + 1,), -1, dtype=torch.int64, device=DEV)
+    needed = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ag.ag_pack_row_off(ctx, df, room, total, row_off, needed)
+    torch.cuda.synchronize()
+    assert np.array_equal(row_off.cpu().numpy(), want_ro) and int(needed.item()) == need
+    packed = ag.KVCache(torch.full((total, D), float("nan"), dtype=torch.bfloat16, device=DEV),
+                        torch.full((total, D), float("nan"), dtype=torch.bfloat16, device=DEV),
+                        torch.full((total,), -1, dtype=torch.int32, device=DEV), row_off,
+                        torch.zeros(B * H, dtype=torch.int32, device=DEV), B, H, D, total_rows=total)
+    out_p = torch.empty_like(dq)
+    ag.ag_compact_prefill_attn(ctx, dq, dk, dv, df, scale, 0, packed, out_p)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    rc, over = oracle.compact_kv(k.storage, v.storage, flags, want_ro)
+    assert over == 0
+    lens = packed.len.cpu().numpy()
+    assert np.array_equal(lens, rc.len) and np.array_equal(np.diff(want_ro), lens + room)
+    from gpu_util import host_bits
+    gk, gv, gi = host_bits(packed.k), host_bits(packed.v), packed.idx.cpu().numpy()
+    for u in range(B * H):
+        a, n = int(want_ro[u]), int(rc.len[u])
+        assert np.array_equal(gk[a:a + n], rc.k[a:a + n]) and np.array_equal(gv[a:a + n], rc.v[a:a + n])
+        assert np.array_equal(gi[a:a + n], rc.idx[a:a + n])
+    # the same attention over full-length slabs
+    slabs = new_cache(B, H, D, torch.bfloat16, oracle.slab_row_off(B * H, L))
+    out_s = torch.empty_like(dq)
+    ag.ag_compact_prefill_attn(ctx, dq, dk, dv, df, scale, 0, slabs, out_s)
+    torch.cuda.synchronize()
+    assert torch.equal(out_p, out_s)
+    # decoding into the spare rows
+    ref = oracle.Cache(W.bf16_bits_to_f32(rc.k), W.bf16_bits_to_f32(rc.v), rc.idx.copy(), want_ro.copy(), rc.len.copy())
+    o = torch.empty(B, H, D, dtype=torch.bfloat16, device=DEV)
+    for s in range(room + 1):
+        qs, kn, vn = (W.store(g.standard_normal((B, H, D)).astype(np.float32), "bf16") for _ in range(3))
+        ag.ag_decode_attn(ctx, dev(qs), dev(kn), dev(vn), None, L + s, scale, packed, o)
+        want, dropped = oracle.decode_step(qs.f32, kn.f32, vn.f32, None, L + s, ref, scale)
+        got = host_f32(o)
+        assert np.isfinite(got).all() and attn_error("bf16", got, want) <= attn_tolerance("bf16")
+        assert np.array_equal(packed.len.cpu().numpy(), ref.len)
+        assert dropped == (B * H if s == room else 0)
+    with pytest.raises(ag.AgError) as e:
+        ctx.poll_error()
+    assert e.value.status == ag.AG_ECAPACITY
+    assert np.array_equal(packed.len.cpu().numpy(), rc.len + room)
+    ctx.close()
+
+
+def test_packed_cache_layout_cut_off_at_the_allocation():
+    """An allocation smaller than the layout needs: the offsets stop at total_rows, the units past the end get no
+    rows, the compaction drops theirs (AG_ECAPACITY) exactly as the oracle's does with the same offsets, and the
+    needed-rows word tells the caller what would have been enough."""
+    B, H, L, D = 2, 4, 300, 64
+    g = np.random.default_rng(401)
+    k, v = (W.store(g.standard_normal((B, H, L, D)).astype(np.float32), "f32") for _ in range(2))
+    flags = (g.random((B, H, L)) < 0.5).astype(np.uint8)
+    want_all, need = oracle.packed_row_off(flags, 4, 10 ** 9)
+    total = int(want_all[5]) + 7            # ends 7 rows into unit 5
+    want_ro, _ = oracle.packed_row_off(flags, 4, total)
+    ctx = make_ctx(B, L, H, H, D, ag.AG_F32, cache_rows=total)
+    row_off = torch.zeros(B * H + 1, dtype=torch.int64, device=DEV)
+    needed = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ag.ag_pack_row_off(ctx, dev(flags), 4, total, row_off, needed)
+    cache = ag.KVCache(torch.zeros(total, D, device=DEV), torch.zeros(total, D, device=DEV),
+                       torch.full((total,), -1, dtype=torch.int32, device=DEV), row_off,
+                       torch.zeros(B * H, dtype=torch.int32, device=DEV), B, H, D, total_rows=total)
+    ag.ag_compact_kv(ctx, dev(k), dev(v), dev(flags), 0, cache)
+    torch.cuda.synchronize()
+    assert np.array_equal(row_off.cpu().numpy(), want_ro) and int(needed.item()) == need > total
+    with pytest.raises(ag.AgError) as e:
+        ctx.poll_error()
+    assert e.value.status == ag.AG_ECAPACITY
+    rc, over = oracle.compact_kv(k.f32, v.f32, flags, want_ro)
+    assert over == 3 and np.array_equal(cache.len.cpu().numpy(), rc.len) and rc.len[5] == 7 and (rc.len[6:] == 0).all()
+    assert np.array_equal(cache.k.cpu().numpy()[:total], rc.k[:total])
+    ctx.close()
