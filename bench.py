@@ -14,8 +14,8 @@ The step is timed over --steps launches without instrumentation (eager by defaul
 graph).  Kernel durations for the roofline come from HIP event pairs that the library records around every
 kernel on the launch stream (ag_timing_* of the C ABI) over the same number of steps right after.
   machine       : what this machine sustains (MFMA loop, streaming copy, vendor bf16 GEMM) beside the data-sheet peaks.
-Optional legs: --config 4 / --config 5 --layer l (the other layer workloads), --keep, --seq-len, --decode-stack
-(config 5's decode phase: one token through 32 layers, eager and from a HIP graph), --project (the K/V projection
+Optional legs: --config 4 / --config 5 --layer l (the other layer workloads), --keep, --seq-len, --config5-stack
+(config 5 end to end: the prompt, then 256 decode steps, through all 32 layers), --project (the K/V projection
 with the compaction in its epilogue), --norm-gate (the gate fused with the normalisation of its input), --power (package power under the prefill kernel),
 next_layer_gate_overlap (the next layer's gate on a second stream).
 """
@@ -144,6 +144,13 @@ def prefill_leg(args, torch, ag, W):
     ctx.timing_enable(False)
     ctx.poll_error()
 
+    # what the parity bar sets aside: gate logits within 1e-3 of the threshold (their flags may legitimately differ from
+    # a reference computed in another precision), counted on one untimed gate call that also writes the logits
+    logits = torch.empty(B, L, Hkv, dtype=torch.float32, device="cuda")
+    ag.ag_gate(ctx, x, wg, bias, wl.tau, wl.n_sink, logits, flags)
+    thr = math.log(wl.tau / (1.0 - wl.tau))
+    near = int(((logits - thr).abs() < 1e-3).sum().item())
+    gate_keep = flags.float().mean(dim=(0, 2)).cpu().numpy()
     fl = pf_flags.cpu().numpy()
     pairs = visible_pairs(fl, G)
     flops = 4.0 * D * pairs
@@ -159,6 +166,9 @@ def prefill_leg(args, torch, ag, W):
         "tokens": B * L * args.steps,
         "kernel_ms": per_kernel,
         "keep_ratio": float(fl.mean()),
+        "keep_ratio_per_head": [round(float(r), 4) for r in fl.mean(axis=(0, 2))],
+        "gate": {"near_threshold_logits": near, "logits": int(logits.numel()), "band": 1e-3,
+                 "keep_ratio_per_head": [round(float(r), 4) for r in gate_keep]},
         "roofline": {"kernel": "ag_prefill_d128_kernel<%d, false, 4>" % min(4, G), "bound": "mfma", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": TRAFFIC_BYTES.get(("prefill", L)) if args.keep is None and args.config == 2 else None, "flops_per_launch": flops, "visible_pairs": pairs,
@@ -290,83 +300,84 @@ def decode_leg(args, torch, ag, W):
     return res, wl
 
 
-def decode_stack_leg(args, torch, ag, W):
-    """Config 5's decode phase: one token through 32 layers = 32 ag_decode_attn calls on 32 ragged caches
-    (B = 16, 32 heads x 128; kept rows per layer from config5_decode_lens), eager and replayed from a HIP graph.
-    Cache contents are seeded N(0,1) drawn on the device (their values do not change the traffic)."""
-    layers, B, H, D, steps = 32, 16, 32, 128, args.stack_steps
-    U = B * H
+def config5_stack_leg(args, torch, ag, W):
+    """Config 5 end to end: the 32-layer attention path (no MLPs), B = 16, prompt L = 2048, then 256 decode steps,
+    with gate, compaction, masked attention and ragged decode on every layer.  Each layer has its own gate (the
+    weights, per-head biases and dead heads of workloads.config5_layer; keep falls from 0.9 to 0.1 with depth) and
+    its own activations, seeded N(0, 1) (x: 0.5 N(0, 1)) drawn on the device -- their values do not change the work,
+    the flags the gate makes of them do.  The caches use the packed layout (ag_pack_row_off: retained rows + room
+    for the generated tokens per unit), sized from an untimed pass of the gates.
+    Timed: (1) the prompt through all 32 layers (gate -> packed offsets -> compaction + attention per layer);
+    (2) `--stack-tokens` decode steps through all 32 layers (every generated token kept)."""
+    layers, B, H, D, L, d = args.stack_layers, 16, 32, 128, 2048, 4096
+    tokens = args.stack_tokens
+    U, room = B * H, tokens + 8
     gen = torch.Generator(device="cuda")
     gen.manual_seed(5)
-    caches, rows = [], 0
-    for l in range(layers):
-        len0 = W.config5_decode_lens(l, B)
-        cap = len0.astype(np.int64) + steps + 16
-        ro = np.zeros(U + 1, dtype=np.int64)
-        np.cumsum(cap, out=ro[1:])
-        total = int(ro[-1])
-        k = torch.randn(total, D, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
-        v = torch.randn(total, D, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
-        caches.append(ag.KVCache(k, v, torch.zeros(total, dtype=torch.int32, device="cuda"), torch.from_numpy(ro).cuda(),
-                                 torch.from_numpy(len0).cuda(), B, H, D, total_rows=total))
-        rows = max(rows, total)
-    ctx = ag.Context(0, ag.workspace_bytes(B, 1, H, H, D, ag.AG_BF16, 0, rows))
-    q, kn, vn = (torch.randn(B, H, D, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
-    outs = [torch.empty(B, H, D, dtype=torch.bfloat16, device="cuda") for _ in range(layers)]
     scale = 1.0 / math.sqrt(D)
+    ctx = ag.Context(0, ag.workspace_bytes(B, L, H, H, D, ag.AG_BF16, d, U * (L + room)))
+    lay = []
+    for l in range(layers):
+        w, bias, keep, dead = W.config5_gate_params(l)
+        x = (0.5 * torch.randn(B, L, d, device="cuda", generator=gen)).to(torch.bfloat16)
+        q, k, v = (torch.randn(B, H, L, D, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
+        flags = torch.empty(B, H, L, dtype=torch.uint8, device="cuda")
+        ag.ag_gate(ctx, x, to_dev(w, torch), torch.from_numpy(bias).cuda(), 0.5, 0, None, flags)
+        kept = int(flags.sum().item())               # untimed sizing pass: rows this layer's cache needs
+        total = kept + U * room
+        cache = ag.KVCache(torch.zeros(total, D, dtype=torch.bfloat16, device="cuda"),
+                           torch.zeros(total, D, dtype=torch.bfloat16, device="cuda"),
+                           torch.zeros(total, dtype=torch.int32, device="cuda"),
+                           torch.zeros(U + 1, dtype=torch.int64, device="cuda"),
+                           torch.zeros(U, dtype=torch.int32, device="cuda"), B, H, D, total_rows=total)
+        lay.append(dict(x=x, w=to_dev(w, torch), bias=torch.from_numpy(bias).cuda(), q=q, k=k, v=v, flags=flags,
+                        cache=cache, total=total, kept=kept, out=torch.empty_like(q), dead=int(dead.sum())))
+    dq, dk, dv = (torch.randn(B, H, D, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
+    dout = torch.empty(B, H, D, dtype=torch.bfloat16, device="cuda")
 
-    def token():
-        for l in range(layers):
-            ag.ag_decode_attn(ctx, q, kn, vn, None, 2048, scale, caches[l], outs[l])
+    def prompt():
+        for a in lay:
+            ag.ag_gate(ctx, a["x"], a["w"], a["bias"], 0.5, 0, None, a["flags"])
+            ag.ag_pack_row_off(ctx, a["flags"], room, a["total"], a["cache"].row_off)
+            ag.ag_compact_prefill_attn(ctx, a["q"], a["k"], a["v"], a["flags"], scale, 0, a["cache"], a["out"])
 
-    def lens():
-        return torch.stack([c.len for c in caches]).clone()
+    def decode(n):
+        for s in range(n):
+            for a in lay:
+                ag.ag_decode_attn(ctx, dq, dk, dv, None, L + s, scale, a["cache"], dout)
 
-    def set_lens(x):
-        for l, c in enumerate(caches):
-            c.len.copy_(x[l])
-
-    token()
+    prompt()
     torch.cuda.synchronize()
-    # graph of one token; replays checked against the eager token from the same lengths
-    start = lens()
-    token()
-    torch.cuda.synchronize()
-    ref = [o.clone() for o in outs]
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    graph = torch.cuda.CUDAGraph()
-    set_lens(start)
-    with torch.cuda.graph(graph, stream=side):
-        token()
-    torch.cuda.current_stream().wait_stream(side)
-    for r in range(3):
-        set_lens(start)
-        for o in outs:
-            o.zero_()
-        graph.replay()
-        torch.cuda.synchronize()
-        if not all(torch.equal(a, b) for a, b in zip(outs, ref)):
-            raise RuntimeError("decode graph replay %d differs from the eager token" % r)
-        token()  # eager work between replays
-        torch.cuda.synchronize()
-    res = {}
-    for name, run in (("eager", token), ("graph", graph.replay)):
-        set_lens(start)
-        torch.cuda.synchronize()
-        before = int(lens().sum())
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            run()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        after = int(lens().sum())
-        byts = 0.5 * (before + after) * D * 2 * 2
-        res[name] = {"ms_per_token": dt / steps * 1e3, "gbs": byts * steps / dt / 1e9}
     ctx.poll_error()
+    t0 = time.perf_counter()
+    prompt()
+    torch.cuda.synchronize()
+    t_prompt = time.perf_counter() - t0
+    ctx.poll_error()
+    rows0 = sum(int(a["cache"].len.sum().item()) for a in lay)
+    assert rows0 == sum(a["kept"] for a in lay)
+    decode(2)       # warm-up steps (their rows stay in the caches; the timed steps follow on)
+    torch.cuda.synchronize()
+    rows1 = sum(int(a["cache"].len.sum().item()) for a in lay)
+    t0 = time.perf_counter()
+    decode(tokens)
+    torch.cuda.synchronize()
+    t_dec = time.perf_counter() - t0
+    ctx.poll_error()
+    rows2 = sum(int(a["cache"].len.sum().item()) for a in lay)
+    assert rows2 == rows1 + tokens * U * layers
+    byts = 0.5 * (rows1 + rows2) * D * 2 * 2      # K and V rows read per token, mean of first and last step
     ctx.close()
-    return {"workload": "cfg5_decode_32_layers_B16", "tokens": steps, "launches_per_token": 2 * layers,
-            "bytes_per_token": byts, **{k + "_" + kk: vv for k, v in res.items() for kk, vv in v.items()}}
+    return {"workload": "cfg5_stack_%d_layers_B16_L2048" % layers, "layers": layers, "prompt_tokens": B * L,
+            "cache_layout": "packed (ag_pack_row_off), %d spare rows per unit" % room,
+            "kept_rows_after_prompt": rows0, "keep_ratio_mean": rows0 / (layers * U * L),
+            "cache_bytes": sum(a["total"] for a in lay) * D * 2 * 2, "slab_cache_bytes": layers * U * (L + room) * D * 2 * 2,
+            "dead_heads": sum(a["dead"] for a in lay),
+            "prompt_ms_all_layers": t_prompt * 1e3, "prompt_tokens_per_s": B * L / t_prompt,
+            "decode_tokens": tokens, "decode_ms_per_token": t_dec / tokens * 1e3,
+            "decode_tokens_per_s": B * tokens / t_dec, "decode_bytes_per_token": byts,
+            "decode_gbs": byts * tokens / t_dec / 1e9, "decode_launches_per_token": 2 * layers,
+            "seconds_prompt_plus_decode": t_prompt + t_dec}
 
 
 def projection_leg(args, torch, ag, W, wl):
@@ -655,9 +666,11 @@ def main():
                     help="also time the gate fused with the RMS normalisation of its input (ag_rmsnorm_gate)")
     ap.add_argument("--power", action="store_true",
                     help="also sample the package power sensor while the prefill kernel runs back to back")
-    ap.add_argument("--decode-stack", action="store_true",
-                    help="also time config 5's decode phase (one token through 32 layers, eager and from a HIP graph)")
-    ap.add_argument("--stack-steps", type=int, default=32)
+    ap.add_argument("--config5-stack", "--decode-stack", dest="config5_stack", action="store_true",
+                    help="also run config 5 end to end: the prompt through all 32 layers, then --stack-tokens decode "
+                         "steps through all 32 layers (about 45 GB of activations and caches on the device)")
+    ap.add_argument("--stack-tokens", type=int, default=256)
+    ap.add_argument("--stack-layers", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching it eagerly")
     ap.add_argument("--repeats", type=int, default=5,
                     help="times the timed block of --steps steps (and the decode leg's block) is repeated; the line "
@@ -702,9 +715,9 @@ def main():
     norm_gate = norm_gate_leg(args, torch, ag, W, wl) if args.norm_gate and wl.x is not None else None
     power = power_leg(args, torch, ag, W, wl) if args.power else None
     stack = None
-    if args.decode_stack:
-        log("[bench] config 5 decode phase, 32 layers ...")
-        stack = decode_stack_leg(args, torch, ag, W)
+    if args.config5_stack:
+        log("[bench] config 5 end to end, %d layers ..." % args.stack_layers)
+        stack = config5_stack_leg(args, torch, ag, W)
     machine = None if args.skip_machine else machine_context(torch, ag)
     if machine:
         pre["roofline"]["frac_of_vendor_gemm"] = pre["roofline"]["achieved"] / machine["vendor_gemm_bf16_8192_tflops"]
@@ -719,8 +732,9 @@ def main():
         "config": pre["config"], "kernel_ms": pre["kernel_ms"],
         "ms_per_step_spread": pre["ms_per_step_spread"],
         "ms_per_step_with_kernel_events": pre["seconds_instrumented"] / args.steps * 1e3, "roofline": pre["roofline"],
-        "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "decode": dec, "cpu_baseline": cpu,
-        "next_layer_gate_overlap": overlap, "decode_stack": stack, "kv_projection": proj, "norm_gate": norm_gate, "prefill_power": power, "machine": machine,
+        "compact_gbs": pre["compact_gbs"], "gate_gbs": pre["gate_gbs"], "keep_ratio_per_head": pre["keep_ratio_per_head"],
+        "gate": pre["gate"], "decode": dec, "cpu_baseline": cpu,
+        "next_layer_gate_overlap": overlap, "config5_stack": stack, "kv_projection": proj, "norm_gate": norm_gate, "prefill_power": power, "machine": machine,
     }
     print(json.dumps(line))
 

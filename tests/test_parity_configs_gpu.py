@@ -101,14 +101,13 @@ def test_config4_full_size_gqa_long_prompt():
 
 
 # ------------------------------------------------------------------------------------------------ config 5
-@pytest.mark.parametrize("layer", [0, 31])
-def test_config5_layer_full_size(layer):
-    """One layer of the 32-layer stack at full size (B=16, L=2048, 32 heads): first layer (keep 0.9) and last
-    layer (keep 0.1, several fully evicted heads).  Gate whole, compaction whole, prefill on sampled rows of all
-    512 heads (fully evicted heads: whole output equals V bit for bit), 2 decode steps over all 512 caches."""
-    wl = W.config5_layer(layer)
+def _config5_layer_check(layer, B, steps=2, n_rows=4):
+    """One layer of config 5 through the whole path against the oracle: gate whole, compaction whole, prefill on
+    sampled rows of every head (fully evicted heads: whole output equals V bit for bit), decode steps over all
+    caches.  With B < 16 the inputs are the first B sequences of the layer's B = 16 draw (the generator fills
+    sequence after sequence), i.e. a subset of the configuration's (layer, sequence, head) units."""
+    wl = W.config5_layer(layer, B=B)
     B, L, H, D, d = wl.B, wl.L, wl.Hq, wl.D, wl.d_model
-    steps = 2
     ctx = make_ctx(B, L, H, H, D, ag.AG_BF16, d_in=d, cache_rows=B * H * (L + steps))
     flags = torch.empty(B, H, L, dtype=torch.uint8, device=DEV)
     logits = torch.empty(B, L, H, dtype=torch.float32, device=DEV)
@@ -134,10 +133,31 @@ def test_config5_layer_full_size(layer):
     ctx.poll_error()
     for h in np.nonzero(~live)[0]:
         assert torch.equal(out[:, h], dv[:, h])            # fully evicted head: every row is its own value
-    check_sampled_rows(host_f32(out), wl.q, wl.k, wl.v, fl, wl.scale, sample_rows(L, 50 + layer, 4),
+    check_sampled_rows(host_f32(out), wl.q, wl.k, wl.v, fl, wl.scale, sample_rows(L, 50 + layer, n_rows),
                        "cfg5 layer %d prefill" % layer)
     decode_and_check(ctx, wl, cache, ref, ro, steps, 60 + layer, 0.5)
     ctx.close()
+    return int((~live).sum())
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_config5_layer_full_size(layer):
+    """One layer of the 32-layer stack at full size (B=16, L=2048, 32 heads): first layer (keep 0.9) and last
+    layer (keep 0.1, several fully evicted heads)."""
+    _config5_layer_check(layer, 16)
+
+
+@pytest.mark.timeout(600)
+def test_config5_every_layer_with_dead_heads_on_two_sequences_each():
+    """Config 5's deep layers (24 to 31, where about a tenth of the heads are fully evicted): the first two sequences
+    of every such layer through gate, compaction, prefill and decode -- 8 layers x 2 sequences x 32 heads = 512
+    (layer, sequence, head) units, every dead head among them -- and every second shallower layer on one sequence."""
+    dead = 0
+    for layer in range(24, 32):
+        dead += _config5_layer_check(layer, 2, n_rows=2)
+    assert dead >= 8                      # the recipe gives each deep layer about three dead heads
+    for layer in range(2, 24, 2):
+        _config5_layer_check(layer, 1, steps=1, n_rows=0)
 
 
 # ------------------------------------------------------------------------------------------------ config 3

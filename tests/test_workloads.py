@@ -59,3 +59,14 @@ def test_config5_decode_lens_follow_the_layer_keep_ratios():
         assert np.array_equal(W.config5_decode_lens(layer), lens.reshape(-1))   # seeded
     dead = (W.config5_decode_lens(31).reshape(16, 32) == 0).all(0)
     assert dead.sum() >= 1   # fully evicted heads in the deepest layer, the same heads for every sequence
+
+
+def test_config5_gate_params_are_the_layers_own():
+    """The light-weight accessor gives the same gate (weights, bias, dead heads) as the full layer workload."""
+    import numpy as np
+    import workloads as W
+    for layer in (3, 27):
+        wl = W.config5_layer(layer, B=1, L=8)
+        w, bias, keep, dead = W.config5_gate_params(layer)
+        assert np.array_equal(w.bits, wl.w_gate.bits) and np.array_equal(bias, wl.bias)
+        assert np.array_equal(dead, wl.extra["dead_heads"]) and np.allclose(keep, wl.keep)

@@ -287,6 +287,20 @@ def decode_batch(config: int, name: str, dtype: str, B: int, Hq: int, Hkv: int, 
                           store(k, dtype), store(v, dtype), idx, pos0)
 
 
+def config5_gate_params(layer: int, n_layers: int = 32):
+    """The gate of one layer of config 5 without the layer's activations: (w_gate, bias, target keep per head, dead
+    heads), the same draws as config5_layer makes (for benchmarks that fill the activations on the device)."""
+    H, d = 32, 4096
+    g = rng(5, 1000 + layer)
+    rho = 0.9 - 0.8 * layer / (n_layers - 1)
+    keep = np.clip(rho + 0.05 * (g.random(H) - 0.5), 0.02, 0.98)
+    dead = (g.random(H) < 0.10) if layer >= 24 else np.zeros(H, dtype=bool)
+    w_gate = store(normal(5, 100 * (layer + 1) + 2, (d, H), 1.0 / math.sqrt(d)), "bf16")
+    bias = gate_bias_for_keep(w_gate.f32, 0.5, keep, 0.5)
+    bias = np.where(dead, np.float32(-1.0e4), bias).astype(np.float32)
+    return w_gate, bias, np.where(dead, 0.0, keep), dead
+
+
 def config5_decode_lens(layer: int, B: int = 16, L: int = 2048, n_layers: int = 32) -> np.ndarray:
     """Kept rows per (batch, head) unit of layer `layer` after a 2048-token prompt, for the 32-layer decode
     phase: the layer's per-head keep ratios are those of config5_layer (fully evicted heads included), each
