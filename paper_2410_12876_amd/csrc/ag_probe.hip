@@ -32,6 +32,43 @@ __global__ __launch_bounds__(256) void ag_probe_mfma_kernel(int iters, float *si
   if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; practically never true
 }
 
+// The same loop on operands that change from one MFMA to the next and look like data: eight A and eight B fragments
+// per lane with pseudo-random signs, mantissas and exponents (values of magnitude 1/4 .. 4), cycled so that
+// consecutive MFMAs of the matrix pipe never see the same inputs.  The power an MFMA draws depends on how many
+// bits toggle, so this is the ceiling that applies to a kernel working on real activations.
+__global__ __launch_bounds__(256) void ag_probe_mfma_data_kernel(int iters, float *sink) {
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  uint4 a[8], b[8];
+  uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+  auto next = [&]() {  // two bf16 with random sign and mantissa, exponent 125..128
+    h = h * 1664525u + 1013904223u;
+    const uint32_t lo = (h & 0x807fu) | ((125u + ((h >> 8) & 3u)) << 7);
+    const uint32_t hi = ((h >> 16) & 0x807fu) | ((125u + ((h >> 24) & 3u)) << 7);
+    return lo | (hi << 16);
+  };
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = make_uint4(next(), next(), next(), next());
+    b[j] = make_uint4(next(), next(), next(), next());
+  }
+  for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[j]),
+                                                           __builtin_bit_cast(bf16x8, b[(j * 3 + 1) & 7]), acc[j & 3], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  if (s == 12345.678f) sink[0] = s;
+}
+
 __global__ __launch_bounds__(256) void ag_probe_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
                                                             size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -42,8 +79,19 @@ __global__ __launch_bounds__(256) void ag_probe_copy_kernel(const uint4 *__restr
 
 extern "C" {
 
+static ag_status probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, bool data, double *tflops);
+
 ag_status ag_probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, double *tflops) {
+  return probe_mfma(ctx, hip_stream, iters, false, tflops);
+}
+
+ag_status ag_probe_mfma_data(ag_ctx *ctx, void *hip_stream, int iters, double *tflops) {
+  return probe_mfma(ctx, hip_stream, iters, true, tflops);
+}
+
+static ag_status probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, bool data, double *tflops) {
   if (!ctx || !tflops || iters <= 0) return AG_EINVAL;
+  iters = (iters + 1) & ~1;
   if (ctx->device < 0) return ag_fail(ctx, AG_EHIP, "context has no device");
   hipStream_t s = (hipStream_t)hip_stream;
   hipEvent_t e0, e1;
@@ -51,9 +99,10 @@ ag_status ag_probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, double *tflops
     return ag_fail(ctx, AG_EHIP, "ag_probe_mfma: event creation failed");
   const int blocks = ctx->num_cu * 2;  // 8 waves per CU, 2 per SIMD
   float *sink = reinterpret_cast<float *>(ctx->d_err) + 8;
-  hipLaunchKernelGGL(ag_probe_mfma_kernel, dim3(blocks), dim3(256), 0, s, iters / 8 + 1, sink);  // warm-up
+  auto kernel = data ? ag_probe_mfma_data_kernel : ag_probe_mfma_kernel;
+  hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, s, (iters / 8 + 2) & ~1, sink);  // warm-up
   (void)hipEventRecord(e0, s);
-  hipLaunchKernelGGL(ag_probe_mfma_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
+  hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
   (void)hipEventRecord(e1, s);
   float ms = 0.f;
   hipError_t e = hipEventSynchronize(e1);
