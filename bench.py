@@ -621,8 +621,8 @@ def cpu_baseline(wl, W):
 # profiles/bench_cfg2_prefill_cfg3_decode_hbm_traffic.md (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE, in KiB, the
 # factors calibrated on the 1 GiB copy kernel); they hold for the default workloads only.
 TRAFFIC_BYTES = {
-    ("prefill", 4096): int((2.0 * 68329 + 39508) * 1024),
-    ("decode", 32, 256): int((2.0 * 576177 + 10507) * 1024),
+    ("prefill", 4096): int((2.0 * 66388 + 39503) * 1024),
+    ("decode", 32, 256): int((2.0 * 576164 + 10405) * 1024),
 }
 
 

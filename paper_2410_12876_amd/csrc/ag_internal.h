@@ -68,6 +68,27 @@ static inline ag_evpair ag_time_kernel(ag_ctx *ctx, int id) {
       hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                  \
   } while (0)
 
+// ---- How workgroups of ONE launch hand data to each other (prefill chunk states, gate K splits, the planner's
+// per-unit counts) -------------------------------------------------------------------------------------------------
+// Pattern: a producer writes its data, waits until those writes have completed, then bumps an arrival counter with an
+// atomic add; the workgroup that sees the last arrival reads everybody's data.  What makes this hold on gfx950,
+// instruction by instruction:
+//   * The 8 XCDs have an L2 each, and those L2s are not kept coherent with one another inside a kernel; a plain store
+//     may sit dirty in its XCD's L2 and a plain load may hit a stale line.  The data that is exchanged is therefore
+//     written ONLY with system-scope atomic stores and read ONLY with system-scope atomic loads, which the compiler
+//     turns into global_store / global_load with the sc0 and sc1 bits set (checked in the generated code): such a store
+//     is written through to memory and such a load is served from memory, never from a line cached earlier.  That is
+//     the per-access form of what a release fence (write back the whole L2) and an acquire fence (invalidate it) would
+//     do for all lines -- and those two fences were measured to stall every workgroup of the XCD.
+//   * s_waitcnt vmcnt(0) after the stores: a written-through store is counted as complete only when memory has
+//     acknowledged it, so when the counter is bumped (by a thread of the same wave, or after a workgroup barrier that
+//     follows every wave's own wait) the data is in memory.
+//   * The counter itself is a device-scope atomic add (executed in memory-side atomic units, one copy for all XCDs).
+//     The reader's loads are issued after its workgroup has seen the counter's value (a barrier in between), so they
+//     come after the add in time, and being served from memory they observe everything written before it.
+// In the language's terms the accesses are relaxed atomics ordered by that argument about the hardware, not by
+// release/acquire semantics; the tests that alternate launches under concurrent memory traffic and compare bits guard it.
+
 // Bump allocator over the context's workspace; every block is 256-byte aligned.
 struct ws_cursor {
   char *base;
