@@ -652,8 +652,8 @@ def machine_context(torch, ag):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, choices=[2, 4, 5],
                     help="prefill workload: 2 = headline (default); 4, 5 = the other layer-shaped configurations")
     ap.add_argument("--layer", type=int, default=16, help="layer of config 5")

@@ -165,6 +165,13 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
                                   const ag_pf_plan &plan, float *part, bool out_token_major = false,
                                   ag_evpair ev = ag_evpair{nullptr, nullptr});
 
+// The 64-queries-per-wave variant of the same kernel (experiment, AG_PREFILL_Q64=1; n_recent = 1 only): same plan,
+// same grid of `blocks` workgroups, 128 threads each.
+hipError_t ag_launch_prefill_d128_q64(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
+                                      const int32_t *blk_off, int L, int Hq, int Hkv, float qscale, const void *kc,
+                                      const void *vc, const int64_t *row_off, void *out, const ag_pf_plan &plan,
+                                      float *part, bool out_token_major, ag_evpair ev, unsigned blocks);
+
 // RMS normalisation of h (weights g, bf16, d_in <= 8192) fused with the gate; x_out may be h itself.
 hipError_t ag_launch_norm_gate(ag_ctx *ctx, hipStream_t s, const void *h, int B, int L, int d_in, const void *g,
                                float eps, const void *w, const float *bias, int H_f, float thr, int n_sink,
