@@ -169,7 +169,7 @@ def prefill_leg(args, torch, ag, W):
         "keep_ratio_per_head": [round(float(r), 4) for r in fl.mean(axis=(0, 2))],
         "gate": {"near_threshold_logits": near, "logits": int(logits.numel()), "band": 1e-3,
                  "keep_ratio_per_head": [round(float(r), 4) for r in gate_keep]},
-        "roofline": {"kernel": "ag_prefill_d128_kernel<%d, false, 4>" % min(4, G), "bound": "mfma", "achieved": ach,
+        "roofline": {"kernel": "ag_prefill_bf16_kernel<128, %d, false, 4>" % min(4, G), "bound": "mfma", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": TRAFFIC_BYTES.get(("prefill", L)) if args.keep is None and args.config == 2 else None, "flops_per_launch": flops, "visible_pairs": pairs,
                      "avg_launch_ms": pf_ms},
@@ -621,7 +621,7 @@ def cpu_baseline(wl, W):
 # profiles/bench_cfg2_prefill_cfg3_decode_hbm_traffic.md (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE, in KiB, the
 # factors calibrated on the 1 GiB copy kernel); they hold for the default workloads only.
 TRAFFIC_BYTES = {
-    ("prefill", 4096): int((2.0 * 66388 + 39503) * 1024),
+    ("prefill", 4096): int((2.0 * 66377 + 39503) * 1024),
     ("decode", 32, 256): int((2.0 * 576164 + 10405) * 1024),
 }
 

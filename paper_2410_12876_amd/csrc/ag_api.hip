@@ -180,12 +180,12 @@ size_t ag_workspace_bytes(int B, int L, int Hq, int Hkv, int D, ag_dtype dtype, 
   // prefill without a cache compacts into the workspace: K, V rows, idx, row_off, len
   const size_t rows = (size_t)units * L;
   size_t plan_bytes = 0;
-  if (dtype == AG_BF16 && D == 128) {  // sizes only: a cursor over no memory counts what the plan would take
+  if (dtype == AG_BF16 && (D == 128 || D == 64)) {  // sizes only: a cursor over no memory counts what the plan would take
     ws_cursor count{nullptr, ~size_t(0) >> 1, 0, true};
     ag_pf_plan plan;
     float *part;
-    ag_prefill_d128_plan(1024 /* upper bound on CUs: the split only shrinks with fewer */, B, L, Hq, Hkv, count, &plan,
-                         &part);
+    ag_prefill_bf16_plan(1024 /* upper bound on CUs: the split only shrinks with fewer */, B, L, Hq, Hkv, D, count,
+                         &plan, &part);
     plan_bytes = count.off;
   }
   const size_t prefill = scan + 2 * ag_align256(rows * D * ag_dtype_size(dtype)) + ag_align256(rows * 4) +
@@ -435,8 +435,8 @@ ag_status prefill_common(ag_ctx *ctx, void *hip_stream, const void *q, const voi
   ag_pf_plan plan;
   memset(&plan, 0, sizeof(plan));
   float *part = nullptr;
-  const bool tuned = dtype == AG_BF16 && D == 128;
-  if (tuned) ag_prefill_d128_plan(ctx->num_cu, B, L, Hq, Hkv, ws, &plan, &part);
+  const bool tuned = dtype == AG_BF16;  // (D = 128 or 64: ag_prefill_supported)
+  if (tuned) ag_prefill_bf16_plan(ctx->num_cu, B, L, Hq, Hkv, D, ws, &plan, &part);
   AG_REQUIRE(ws.ok, AG_EWORKSPACE, "ag_prefill_attn: workspace of %zu bytes is too small (need %zu)", ctx->ws_bytes,
              ws.off);
   ag_status st = need_device(ctx);

@@ -239,7 +239,7 @@ size_t ag_ws_gate_mha_bytes(int B, int L, int d_model, int hp, int H_f) {
   ws_cursor count{nullptr, ~size_t(0) >> 1, 0, true};
   ag_pf_plan plan;
   float *part;
-  ag_prefill_d128_plan(1024, B, L, hp, hp, count, &plan, &part);
+  ag_prefill_bf16_plan(1024, B, L, hp, hp, 128, count, &plan, &part);
   return 3 * ag_align256(tokens * hp * kDh * 2)      // Q', K', V'
          + ag_align256(tokens * hp * kDh * 2)        // attention output = gate features
          + ag_ws_scan_bytes(units, L) + ag_align256((size_t)(units + 1) * 8) + count.off +
@@ -259,7 +259,7 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
   int64_t *row_off = ws.take<int64_t>(units + 1);
   ag_pf_plan plan;
   float *part = nullptr;
-  ag_prefill_d128_plan(ctx->num_cu, B, L, hp, hp, ws, &plan, &part);
+  ag_prefill_bf16_plan(ctx->num_cu, B, L, hp, hp, 128, ws, &plan, &part);
   if (!ws.ok) return hipSuccess;  // caller reports AG_EWORKSPACE
 
   AG_LAUNCH(ag_time_kernel(ctx, AG_K_MHA_PROJ), ag_proj_gemm_kernel<false>,
@@ -271,7 +271,7 @@ hipError_t ag_launch_gate_mha(ag_ctx *ctx, hipStream_t s, const void *x, int B, 
   if ((e = ag_launch_flag_scan(ctx, s, nullptr, units, L, words, blk_off, &plan)) != hipSuccess) return e;
   if ((e = ag_launch_slab_offsets(s, row_off, units, L)) != hipSuccess) return e;
   // every flag is set, so the compacted rows of a head are its K', V' rows themselves
-  e = ag_launch_prefill_d128(s, qkv, qkv + per, qkv + 2 * per, words, blk_off, B, L, hp, hp, scale * 1.4426950408889634f,
+  e = ag_launch_prefill_bf16(s, qkv, qkv + per, qkv + 2 * per, words, blk_off, B, L, hp, hp, 128, scale * 1.4426950408889634f,
                              1, qkv + per, qkv + 2 * per, row_off, feat, plan, part, /*out_token_major=*/true,
                              ag_time_kernel(ctx, AG_K_MHA_ATTN));
   if (e != hipSuccess) return e;

@@ -115,7 +115,7 @@ size_t ag_ws_scan_bytes(int units, int L);
 size_t ag_ws_gate_bytes(int64_t tokens, int d_in, int H_f, ag_dtype dt);
 size_t ag_ws_decode_bytes(int units, int G, int D, int64_t cache_rows);
 
-// What the flag scan's last workgroup prepares for the D = 128 prefill kernel (all pointers device, nullable):
+// What the flag scan's last workgroup prepares for the bf16 prefill kernel (all pointers device, nullable):
 // the head order that balances XCDs, the number of key tiles per chunk, and zeroed per-item arrival counters.
 struct ag_pf_plan {
   int32_t *order;        // [n_hy] head block at each position of a query-tile row
@@ -156,12 +156,13 @@ hipError_t ag_launch_prefill(ag_ctx *ctx, hipStream_t s, const void *q, const vo
                              ag_dtype dt, float scale, int n_recent, const void *kc, const void *vc,
                              const int64_t *row_off, void *out, const ag_pf_plan &plan, float *part);
 
-// bf16, D = 128: the tuned kernel of ag_prefill_d128.hip (qscale = scale * log2 e).  ag_prefill_d128_plan carves
+// bf16, D = 128 or 64: the kernel of ag_prefill_bf16.hip (qscale = scale * log2 e).  ag_prefill_bf16_plan carves
 // the plan's buffers and the partial-state buffer out of the workspace (plan.n_split == 1: no key split).
-void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &ws, ag_pf_plan *plan, float **part);
-hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
-                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
-                                  const void *kc, const void *vc, const int64_t *row_off, void *out,
+void ag_prefill_bf16_plan(int num_cu, int B, int L, int Hq, int Hkv, int D, ws_cursor &ws, ag_pf_plan *plan,
+                          float **part);
+hipError_t ag_launch_prefill_bf16(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
+                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D, float qscale,
+                                  int n_recent, const void *kc, const void *vc, const int64_t *row_off, void *out,
                                   const ag_pf_plan &plan, float *part, bool out_token_major = false,
                                   ag_evpair ev = ag_evpair{nullptr, nullptr});
 

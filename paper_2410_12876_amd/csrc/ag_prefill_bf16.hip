@@ -38,7 +38,7 @@
 
 #include <algorithm>
 
-#include "ag_prefill_d128_common.h"
+#include "ag_prefill_bf16_common.h"
 
 
 namespace {
@@ -51,17 +51,22 @@ namespace {
 // through the same pipeline ahead of the compacted tiles of chunk 0, with their own mask.
 // NW = waves per workgroup: 4 (two workgroups per CU).  (8, one workgroup per CU with twice the queries sharing
 // every K/V tile, also works without the band variant but is slower: the whole CU then moves in step.)
-template <int GB, bool BAND, int NW>
-__global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
+template <int D, int GB, bool BAND, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_bf16_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint64_t *__restrict__ words, const int32_t *__restrict__ blk_off, const uint16_t *__restrict__ kc,
     const uint16_t *__restrict__ vc, const int64_t *__restrict__ row_off, int L, int Hq, int Hkv, int nw, int n_hy,
     int n_split, int n_sp, const int32_t *__restrict__ chunk_tiles_dev, float qscale, int n_recent,
     const int32_t *__restrict__ order, int head_major, uint16_t *__restrict__ out, int out_token_major,
     float *__restrict__ part, int32_t *__restrict__ tickets) {
+  typedef pf_geom<D> geo;
+  constexpr int kRowB = geo::kRowB, kTileB = geo::kTileB, kGroupB = geo::kGroupB;
+  constexpr int CPR = geo::CPR;  // 16-byte chunks per row: 16 (D = 128) or 8 (D = 64)
+  constexpr int RPI = geo::RPI;  // rows per load or store instruction: 4 or 8
+  auto swz = [](int r) { return geo::swz(r); };
   constexpr int QW = NW / GB;  // query sub-tiles per workgroup
   constexpr int RPW = kBN / NW;  // tile rows each wave loads
-  constexpr int LI = RPW / 4;    // load instructions per wave and tile (4 rows each)
+  constexpr int LI = RPW / RPI;  // load instructions per wave and tile (RPI rows each)
   constexpr int BM = 32 * QW;  // queries per workgroup
   constexpr int KS = D / 16;   // k-steps of S^T
   constexpr int DT = D / 32;   // 32-row tiles of O^T
@@ -191,12 +196,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       __builtin_amdgcn_make_buffer_rsrc((void *)(k + (size_t)u * L * D), 0, BAND ? L * kRowB : 0, 0x00020000);
   const __amdgpu_buffer_rsrc_t vb_rsrc =
       __builtin_amdgcn_make_buffer_rsrc((void *)(v + (size_t)u * L * D), 0, BAND ? L * kRowB : 0, 0x00020000);
-  const int ld_r = lane >> 4;
+  const int ld_r = lane / CPR;
   int ld_off[LI];
 #pragma unroll
   for (int i = 0; i < LI; ++i) {
-    const int r = RPW * w4 + 4 * i + ld_r;
-    ld_off[i] = r * kRowB + (((lane & 15) ^ swz(r)) << 4);  // chunk (lane%16)^swz(r)
+    const int r = RPW * w4 + RPI * i + ld_r;
+    ld_off[i] = r * kRowB + (((lane % CPR) ^ swz(r)) << 4);  // chunk (lane % CPR) ^ swz(r)
   }
   const uint32_t ld_base = (uint32_t)(size_t)((AG_LDS uint8_t *)smem) + w4 * RPW * kRowB;
   auto issue_k = [&](int i_step) {  // K of the tile of step i_step -> K buffer i_step & 1
@@ -205,7 +210,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     const __amdgpu_buffer_rsrc_t rsrc = bnd ? kb_rsrc : k_rsrc;
 #pragma unroll
     for (int i = 0; i < LI; ++i) {
-      const uint32_t dk = ld_base + (i_step & 1) * kTileB + i * 4 * kRowB;
+      const uint32_t dk = ld_base + (i_step & 1) * kTileB + i * RPI * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                    :: "s"(dk), "v"(ld_off[i]), "s"(rsrc), "s"(soff) : "memory");
     }
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     const __amdgpu_buffer_rsrc_t rsrc = bnd ? vb_rsrc : v_rsrc;
 #pragma unroll
     for (int i = 0; i < LI; ++i) {
-      const uint32_t dv = ld_base + 2 * kTileB + (i_step & 1) * kTileB + i * 4 * kRowB;
+      const uint32_t dv = ld_base + 2 * kTileB + (i_step & 1) * kTileB + i * RPI * kRowB;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                    :: "s"(dv), "v"(ld_off[i]), "s"(rsrc), "s"(soff) : "memory");
     }
@@ -234,16 +239,16 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   uint4 qf[KS], kself[KS];
   uint2 vself[DT][4];
   {
-    const int srow = lane >> 4, schunk = lane & 15;
-    constexpr int RP = (kTileB / NW) / 256;  // rows per pass: the wave's corner of V1 holds RP rows of 256 bytes
-    constexpr int NP = 32 / RP;              // passes
-    constexpr int LP = RP / 4;               // whole-line loads per pass
+    const int srow = lane / CPR, schunk = lane % CPR;
+    constexpr int RP = (kTileB / NW) / kRowB;  // rows per pass: the wave's corner of V1 holds RP whole rows
+    constexpr int NP = 32 / RP;                // passes
+    constexpr int LP = RP / RPI;               // whole-row loads per pass (RPI rows each)
     u32x4 sq[NP][LP], sk[NP][LP], sv[NP][LP];
 #pragma unroll
     for (int h = 0; h < NP; ++h)
 #pragma unroll
       for (int j = 0; j < LP; ++j) {
-        const int row = min(j0 + RP * h + 4 * j + srow, L - 1);
+        const int row = min(j0 + RP * h + RPI * j + srow, L - 1);
         // All three loads are unconditional (conditional ones end up in scratch memory).  A row whose k, v are not
         // needed -- a kept token, or any row in a later chunk of a split item -- is pointed at the wave's first row
         // instead, which costs one cache line per wave instead of HBM traffic per row.
@@ -254,6 +259,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       }
     AG_LDS uint8_t *stage = (AG_LDS uint8_t *)smem + 3 * kTileB + w4 * (kTileB / NW);
     const int rr = col % RP;  // this lane's row inside a pass
+    const int rk = geo::key(rr);
     // lanes exchange data through the corner: a wave-level release/acquire pair on each side tells the compiler
     // that one lane's store is another lane's load (the hardware keeps a wave's LDS accesses in order anyway)
     auto wave_sync = [] {
@@ -265,8 +271,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       wave_sync();  // the previous contents have been read
 #pragma unroll
       for (int j = 0; j < LP; ++j) {
-        const int r = 4 * j + srow;
-        *reinterpret_cast<AG_LDS u32x4 *>(stage + r * 256 + ((schunk ^ r) << 4)) = x[j];
+        const int r = RPI * j + srow;
+        *reinterpret_cast<AG_LDS u32x4 *>(stage + r * kRowB + ((schunk ^ geo::key(r)) << 4)) = x[j];
       }
       wave_sync();  // the rows are there for every lane
     };
@@ -281,14 +287,14 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       if (mine) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          qf[ks] = get4(rr * 256 + (((2 * ks + hb) ^ rr) << 4));
+          qf[ks] = get4(rr * kRowB + (((2 * ks + hb) ^ rk) << 4));
       }
       if (chunk == 0) {
         put(sk[h]);
         if (mine) {
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks)
-            kself[ks] = get4(rr * 256 + (((2 * ks + hb) ^ rr) << 4));
+            kself[ks] = get4(rr * kRowB + (((2 * ks + hb) ^ rk) << 4));
         }
         put(sv[h]);
         if (mine) {
@@ -297,7 +303,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4)
             {
-              const u32x2 x = *reinterpret_cast<const AG_LDS u32x2 *>(stage + rr * 256 + (((4 * dt + r4) ^ rr) << 4) + 8 * hb);
+              const u32x2 x = *reinterpret_cast<const AG_LDS u32x2 *>(stage + rr * kRowB + (((4 * dt + r4) ^ rk) << 4) + 8 * hb);
               vself[dt][r4] = make_uint2(x[0], x[1]);
             }
         }
@@ -499,9 +505,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     // V fragment reads run four MFMAs ahead of their use
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < 4 * DT; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-      if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+      if (i < 4 * DT - 4) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
     }
   };
   // Band tiles hold rows this workgroup's queries must not see (kept tokens, tokens outside a query's window) next
@@ -515,17 +521,17 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     AG_LDS uint8_t *vt = (AG_LDS uint8_t *)smem + 2 * kTileB + (i & 1) * kTileB + w4 * RPW * kRowB + lane * 16;
 #pragma unroll
     for (int ii = 0; ii < LI; ++ii) {
-      const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(vt + ii * 4 * kRowB);
+      const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(vt + ii * RPI * kRowB);
       bool bad = false;
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         bad |= (x[e] & 0x7f80u) == 0x7f80u || (x[e] & 0x7f800000u) == 0x7f800000u;
-      const uint32_t row_bad = (uint32_t)(__ballot(bad) >> (16 * ld_r)) & 0xffffu;  // the 16 lanes of my row
+      const uint32_t row_bad = (uint32_t)(__ballot(bad) >> (CPR * ld_r)) & ((1u << CPR) - 1u);  // the CPR lanes of my row
       if (row_bad) {
         const u32x4 z = {0u, 0u, 0u, 0u};
-        *reinterpret_cast<AG_LDS u32x4 *>(vt + ii * 4 * kRowB) = z;
-        const int r = RPW * w4 + 4 * ii + ld_r;
-        if ((lane & 15) == 0) atomicOr(&nf_rows[i][r >> 5], 1u << (r & 31));
+        *reinterpret_cast<AG_LDS u32x4 *>(vt + ii * RPI * kRowB) = z;
+        const int r = RPW * w4 + RPI * ii + ld_r;
+        if ((lane % CPR) == 0) atomicOr(&nf_rows[i][r >> 5], 1u << (r & 31));
       }
     }
   };
@@ -565,12 +571,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       s_tile(i + 1, nxt);   // MFMA stream ...
       softmax_tile(cur);    // ... and an independent VALU stream; the groups below interleave them:
       // 4 K-fragment reads ahead, then per MFMA one more read and a slice of the softmax arithmetic
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      constexpr int NM = 2 * KS, AHEAD = NM / 4;  // MFMAs of S^T; fragment reads issued ahead of them
+      __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
 #pragma unroll
-      for (int n = 0; n < 16; ++n) {
+      for (int n = 0; n < NM; ++n) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (n < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+        if (n < NM - AHEAD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 96 / NM, 0);
       }
       if (any_raise) softmax_raise(cur);
     } else if (vis_cur) {
@@ -597,8 +604,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
   // ---- an item cut into chunks: store this chunk's state; the chunk that arrives last merges and writes ----
   if (n_chunks > 1) {
     const size_t item = (size_t)qtile * n_hy + hy;
-    float *st = part + (item * n_split * NW + w4) * (66 * 64) + lane;  // state of chunk c at st + c * cstride
-    const size_t cstride = (size_t)NW * 66 * 64;
+    float *st = part + (item * n_split * NW + w4) * geo::kState + lane;  // state of chunk c at st + c * cstride
+    const size_t cstride = (size_t)NW * geo::kState;
     // The states travel through memory between workgroups of one launch.  They are written through and read
     // past the caches (system-scope relaxed accesses), so no cache-wide write-back or invalidate is needed: the
     // stores are complete (vmcnt 0) before the workgroup's arrival is counted, and the last arrival reads after it.
@@ -608,8 +615,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         __hip_atomic_store(&mine[(16 * dt + r) * 64], acc_o[dt][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    __hip_atomic_store(&mine[64 * 64], m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    __hip_atomic_store(&mine[65 * 64], l_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(&mine[16 * DT * 64], m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(&mine[(16 * DT + 1) * 64], l_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();  // every wave's state is out, and nobody reads the tile buffers any more
     int *last = reinterpret_cast<int *>(smem);
@@ -620,7 +627,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     auto peek = [](const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); };
     float m = m_run;
     for (int c = 0; c < n_chunks; ++c)
-      if (c != chunk) m = fmaxf(m, peek(&st[c * cstride + 64 * 64]));
+      if (c != chunk) m = fmaxf(m, peek(&st[c * cstride + 16 * DT * 64]));
     // Rounded product + rounded product (never a fused multiply-add), so that the result does not depend on which chunk
     // arrives last: two chunks are one commutative addition of this chunk's registers and the other's state; more
     // are added in chunk order starting from zero, this chunk's own state read back like the others'.
@@ -641,8 +648,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     for (int c = 0; c < n_chunks; ++c) {
       if (n_chunks == 2 && c == chunk) continue;
       const float *sc = st + c * cstride;
-      const float f = __builtin_amdgcn_exp2f(peek(&sc[64 * 64]) - m);
-      l_run = mul_round_add(peek(&sc[65 * 64]), f, l_run);
+      const float f = __builtin_amdgcn_exp2f(peek(&sc[16 * DT * 64]) - m);
+      l_run = mul_round_add(peek(&sc[(16 * DT + 1) * 64]), f, l_run);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -664,7 +671,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
       for (int r4 = 0; r4 < 4; ++r4) {
         const u32x2 o = {pack2(acc_o[dt][4 * r4 + 0] * inv, acc_o[dt][4 * r4 + 1] * inv),
                          pack2(acc_o[dt][4 * r4 + 2] * inv, acc_o[dt][4 * r4 + 3] * inv)};
-        *reinterpret_cast<AG_LDS u32x2 *>(ost + col * kRowB + (((4 * dt + r4) ^ (col & 15)) << 4) + 8 * hb) = o;
+        *reinterpret_cast<AG_LDS u32x2 *>(ost + col * kRowB + (((4 * dt + r4) ^ geo::key(col)) << 4) + 8 * hb) = o;
       }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // one lane's store is another lane's load
     __builtin_amdgcn_wave_barrier();
@@ -676,12 +683,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_d128_kernel(
     const int n_rows = min(32, L - j0);  // <= 0 for a wave past the end of the prompt: nothing is stored
     const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)obase, 0, n_rows > 0 ? (uint32_t)((n_rows - 1) * row_stride + kRowB) : 0u, 0x00020000);
-    const int orow_l = lane >> 4, ochunk = lane & 15;
+    const int orow_l = lane / CPR, ochunk = lane % CPR;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = 4 * i + orow_l;
-      const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(ost + row * kRowB + ((ochunk ^ (row & 15)) << 4));
-      if (row < n_rows) __builtin_amdgcn_raw_buffer_store_b128(x, o_rsrc, orow_l * row_stride + ochunk * 16, i * 4 * row_stride, 0);
+    for (int i = 0; i < 32 / RPI; ++i) {
+      const int row = RPI * i + orow_l;
+      const u32x4 x = *reinterpret_cast<const AG_LDS u32x4 *>(ost + row * kRowB + ((ochunk ^ geo::key(row)) << 4));
+      if (row < n_rows) __builtin_amdgcn_raw_buffer_store_b128(x, o_rsrc, orow_l * row_stride + ochunk * 16, i * RPI * row_stride, 0);
     }
   }
 }
@@ -697,7 +704,7 @@ static bool ag_prefill_q64_enabled() {
 
 // Split policy: only launches too small to hide their longest item behind other work are split; heads are
 // dealt to XCDs by kept rows when there are few enough per XCD for their differences to show.
-void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &ws, ag_pf_plan *plan, float **part) {
+void ag_prefill_bf16_plan(int num_cu, int B, int L, int Hq, int Hkv, int D, ws_cursor &ws, ag_pf_plan *plan, float **part) {
   const int G = Hq / Hkv;
   const int GB = G >= 4 ? 4 : G;
   memset(plan, 0, sizeof(*plan));
@@ -721,7 +728,7 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
   }
   *part = nullptr;
   if (plan->n_split > 1) {
-    *part = ws.take<float>((size_t)items * plan->n_split * plan->NW * 66 * 64);
+    *part = ws.take<float>((size_t)items * plan->n_split * plan->NW * (D / 2 + 2) * 64);
     plan->chunk_tiles = ws.take<int32_t>(64);
     plan->tickets = ws.take<int32_t>((size_t)items);
   }
@@ -748,8 +755,8 @@ void ag_prefill_d128_plan(int num_cu, int B, int L, int Hq, int Hkv, ws_cursor &
   if (plan->order || plan->chunk_tiles) plan->kept = ws.take<int32_t>((size_t)B * Hkv);
 }
 
-hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
-                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, float qscale, int n_recent,
+hipError_t ag_launch_prefill_bf16(hipStream_t s, const void *q, const void *k, const void *v, const uint64_t *words,
+                                  const int32_t *blk_off, int B, int L, int Hq, int Hkv, int D, float qscale, int n_recent,
                                   const void *kc, const void *vc, const int64_t *row_off, void *out,
                                   const ag_pf_plan &plan, float *part, bool out_token_major, ag_evpair ev) {
   (void)B;
@@ -761,21 +768,24 @@ hipError_t ag_launch_prefill_d128(hipStream_t s, const void *q, const void *k, c
   const int64_t blocks = plan.head_major ? (int64_t)((plan.n_hy + 7) / 8) * 8 * n_qt
                                          : (int64_t)plan.n_hy * (plan.n_sp * plan.n_split + (n_qt - plan.n_sp));
   const dim3 grid((unsigned)blocks), block(64 * plan.NW);
-  if (n_recent == 1 && ag_prefill_q64_enabled())  // 64 queries per wave: 2 waves per workgroup, same plan
+  if (D == 128 && n_recent == 1 && ag_prefill_q64_enabled())  // 64 queries per wave: 2 waves per workgroup, same plan
     return ag_launch_prefill_d128_q64(s, q, k, v, words, blk_off, L, Hq, Hkv, qscale, kc, vc, row_off, out, plan, part,
                                       out_token_major, ev, (unsigned)blocks);
-#define AG_PF(GG, BB) AG_PFN(GG, BB, 4)
-#define AG_PFN(GG, BB, NN)                                                                                          \
-  AG_LAUNCH(ev, (ag_prefill_d128_kernel<GG, BB, NN>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k, \
-                     (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, \
-                     Hkv, nw, plan.n_hy, plan.n_split, plan.n_sp, plan.chunk_tiles, qscale, n_recent, plan.order,               \
-                     plan.head_major, (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)
-  if (n_recent > 1) {
-    if (GB == 1) { AG_PF(1, true); } else if (GB == 2) { AG_PF(2, true); } else { AG_PF(4, true); }
-  } else {
-    if (GB == 1) { AG_PF(1, false); } else if (GB == 2) { AG_PF(2, false); } else { AG_PF(4, false); }
-  }
+#define AG_PF(DD, GG, BB)                                                                                            \
+  AG_LAUNCH(ev, (ag_prefill_bf16_kernel<DD, GG, BB, 4>), grid, block, 0, s, (const uint16_t *)q, (const uint16_t *)k,  \
+            (const uint16_t *)v, words, blk_off, (const uint16_t *)kc, (const uint16_t *)vc, row_off, L, Hq, Hkv, nw,  \
+            plan.n_hy, plan.n_split, plan.n_sp, plan.chunk_tiles, qscale, n_recent, plan.order, plan.head_major,        \
+            (uint16_t *)out, out_token_major ? 1 : 0, part, plan.tickets)
+#define AG_PFD(DD)                                                                                   \
+  do {                                                                                               \
+    if (n_recent > 1) {                                                                              \
+      if (GB == 1) { AG_PF(DD, 1, true); } else if (GB == 2) { AG_PF(DD, 2, true); } else { AG_PF(DD, 4, true); }    \
+    } else {                                                                                         \
+      if (GB == 1) { AG_PF(DD, 1, false); } else if (GB == 2) { AG_PF(DD, 2, false); } else { AG_PF(DD, 4, false); } \
+    }                                                                                                \
+  } while (0)
+  if (D == 128) AG_PFD(128); else if (D == 64) AG_PFD(64); else return hipErrorInvalidValue;
+#undef AG_PFD
 #undef AG_PF
-#undef AG_PFN
   return hipGetLastError();
 }

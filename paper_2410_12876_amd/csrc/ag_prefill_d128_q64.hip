@@ -1,9 +1,13 @@
 // Flag-masked causal prefill attention, bf16, head dimension 128: the 64-queries-per-wave variant of the kernel in
 // ag_prefill_d128.hip.  An experiment (selected by AG_PREFILL_Q64=1 in the environment), correct and parity-tested,
 // but slower than the 4-wave kernel as the compiler builds it; kept for the measurement it documents.
-#include "ag_prefill_d128_common.h"
+#include "ag_prefill_bf16_common.h"
 
 namespace {
+
+constexpr int D = 128;
+constexpr int kRowB = pf_geom<D>::kRowB, kTileB = pf_geom<D>::kTileB, kGroupB = pf_geom<D>::kGroupB;
+__device__ __forceinline__ int swz(int r) { return pf_geom<D>::swz(r); }
 
 // The same attention with 64 queries per wave: two waves per workgroup, each owning TWO 32-query groups (for one
 // query head: 64 consecutive queries; for grouped-query attention: the same 32 queries of two heads of the group).

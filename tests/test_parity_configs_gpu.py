@@ -175,8 +175,7 @@ def test_config3_full_batch_all_256_steps_to_the_capacity_edge():
 
 
 # ------------------------------------------------------------------------------- launch shapes of the D=128 kernel
-def _prefill_case(B, Hq, Hkv, L, flags, seed, with_cache=True):
-    D = 128
+def _prefill_case(B, Hq, Hkv, L, flags, seed, with_cache=True, D=128):
     g = np.random.default_rng(seed)
     q, k, v = (W.store(g.standard_normal(s).astype(np.float32), "bf16")
                for s in ((B, Hq, L, D), (B, Hkv, L, D), (B, Hkv, L, D)))
@@ -194,16 +193,19 @@ def _prefill_case(B, Hq, Hkv, L, flags, seed, with_cache=True):
     return q, k, v, out
 
 
-@pytest.mark.parametrize("name,B,Hq,Hkv,L", [
-    ("split in two key chunks, balanced order", 1, 16, 16, 2048),
-    ("few heads: up to 8 key chunks per item, heads not a multiple of 8 (no reordering)", 1, 3, 3, 4096),
-    ("few heads, GQA, long prompt: 4 key chunks", 1, 8, 2, 8192),
-    ("large launch, no split", 4, 32, 32, 2048),
-    ("more than 1024 units (plan off)", 36, 32, 32, 256),
-    ("GQA split", 1, 32, 8, 2048),
-    ("ragged length", 2, 16, 4, 1987),
+@pytest.mark.parametrize("name,B,Hq,Hkv,L,D", [
+    ("split in two key chunks, balanced order", 1, 16, 16, 2048, 128),
+    ("few heads: up to 8 key chunks per item, heads not a multiple of 8 (no reordering)", 1, 3, 3, 4096, 128),
+    ("few heads, GQA, long prompt: 4 key chunks", 1, 8, 2, 8192, 128),
+    ("large launch, no split", 4, 32, 32, 2048, 128),
+    ("more than 1024 units (plan off)", 36, 32, 32, 256, 128),
+    ("GQA split", 1, 32, 8, 2048, 128),
+    ("ragged length", 2, 16, 4, 1987, 128),
+    ("head dimension 64: split in two key chunks, balanced order", 1, 16, 16, 2048, 64),
+    ("head dimension 64: few heads, GQA, 4 key chunks", 1, 8, 2, 8192, 64),
+    ("head dimension 64: many heads, head-major order, ragged length", 5, 32, 32, 700, 64),
 ])
-def test_prefill_d128_launch_shapes(name, B, Hq, Hkv, L):
+def test_prefill_bf16_launch_shapes(name, B, Hq, Hkv, L, D):
     """The workgroup-to-item mapping, the head order and the key-chunk split change with the launch size; every
     variant must give the same rows.  Keep ratios differ strongly between heads (0.05 .. 1.0) so that chunking and
     ordering see uneven work; head 0 keeps everything, head 1 nothing."""
@@ -213,8 +215,8 @@ def test_prefill_d128_launch_shapes(name, B, Hq, Hkv, L):
     flags[:, 0] = 1
     if Hkv > 1:
         flags[:, 1] = 0
-    q, k, v, out = _prefill_case(B, Hq, Hkv, L, flags, 71)
-    check_sampled_rows(host_f32(out), q, k, v, flags, 1.0 / math.sqrt(128), sample_rows(L, 72, 6), name)
+    q, k, v, out = _prefill_case(B, Hq, Hkv, L, flags, 71, D=D)
+    check_sampled_rows(host_f32(out), q, k, v, flags, 1.0 / math.sqrt(D), sample_rows(L, 72, 6), name)
     if Hkv > 1:
         G = Hq // Hkv
         assert torch.equal(out[:, G:2 * G], dev(v)[:, 1:2].expand(-1, G, -1, -1))
