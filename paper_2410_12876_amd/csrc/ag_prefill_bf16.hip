@@ -665,13 +665,19 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_bf16_kernel(
   __syncthreads();  // every wave is done with the K/V tiles
   {
     AG_LDS uint8_t *ost = (AG_LDS uint8_t *)smem + w4 * (32 * kRowB);
+    // (the lane number is laundered through an empty asm so that the addresses below are computed here, from one
+    // register, instead of being shared with the look-alike ones of the query staging and kept alive -- in spill
+    // slots, for the recent-token variant -- across the whole tile loop)
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int col_e = lane_e & 31, hb_e = lane_e >> 5;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const u32x2 o = {pack2(acc_o[dt][4 * r4 + 0] * inv, acc_o[dt][4 * r4 + 1] * inv),
                          pack2(acc_o[dt][4 * r4 + 2] * inv, acc_o[dt][4 * r4 + 3] * inv)};
-        *reinterpret_cast<AG_LDS u32x2 *>(ost + col * kRowB + (((4 * dt + r4) ^ geo::key(col)) << 4) + 8 * hb) = o;
+        *reinterpret_cast<AG_LDS u32x2 *>(ost + col_e * kRowB + (((4 * dt + r4) ^ geo::key(col_e)) << 4) + 8 * hb_e) = o;
       }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // one lane's store is another lane's load
     __builtin_amdgcn_wave_barrier();
@@ -683,7 +689,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void ag_prefill_bf16_kernel(
     const int n_rows = min(32, L - j0);  // <= 0 for a wave past the end of the prompt: nothing is stored
     const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)obase, 0, n_rows > 0 ? (uint32_t)((n_rows - 1) * row_stride + kRowB) : 0u, 0x00020000);
-    const int orow_l = lane / CPR, ochunk = lane % CPR;
+    const int orow_l = lane_e / CPR, ochunk = lane_e % CPR;
 #pragma unroll
     for (int i = 0; i < 32 / RPI; ++i) {
       const int row = RPI * i + orow_l;
