@@ -632,6 +632,8 @@ def machine_context(torch, ag):
     ctx = ag.Context(0, 2 << 30)
     mfma = ctx.probe_mfma(200000)
     mfma_data = ctx.probe_mfma_data(200000)
+    # the matrix pipe alone at lower duty cycles (one wave per SIMD, data-like operands): duty -> TFLOP/s
+    duty = {"%.2f" % (256.0 / (256 + 64 * idle)): ctx.probe_mfma_duty(idle, 200000 // (1 + idle // 2)) for idle in (0, 1, 2, 3, 4)}
     copy = ctx.probe_copy(1 << 30)
     ctx.close()
     a = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
@@ -645,7 +647,8 @@ def machine_context(torch, ag):
     e1.record()
     torch.cuda.synchronize()
     gemm = 10 * 2 * 8192 ** 3 / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    return {"mfma_loop_tflops": mfma, "mfma_loop_random_operands_tflops": mfma_data, "hbm_copy_gbs_1GiB": copy,
+    return {"mfma_loop_tflops": mfma, "mfma_loop_random_operands_tflops": mfma_data,
+            "mfma_loop_random_operands_tflops_by_duty": duty, "hbm_copy_gbs_1GiB": copy,
             "vendor_gemm_bf16_8192_tflops": gemm}
 
 

@@ -38,6 +38,11 @@ ag_status ag_probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, double *tflops
  * MFMA to the next): an MFMA's power depends on how many bits toggle, and under the board's power cap that decides
  * the clock.  This is the ceiling that applies to a kernel working on real activations. */
 ag_status ag_probe_mfma_data(ag_ctx *ctx, void *hip_stream, int iters, double *tflops);
+/* The data-operand loop with ONE wave per SIMD (4 per CU) that sleeps `idle` x 64 cycles (0 <= idle <= 64) after
+ * every 8 MFMAs, i.e. with the matrix pipe busy 256 / (256 + 64 idle) of the time and nothing else running.  The
+ * rate at a given duty cycle, compared with duty x (rate at idle = 0), shows how far the chip raises its clock when
+ * the pipe is busy less often: what a kernel at that duty cycle could reach if its other work cost no power. */
+ag_status ag_probe_mfma_duty(ag_ctx *ctx, void *hip_stream, int iters, int idle, double *tflops);
 ag_status ag_probe_copy(ag_ctx *ctx, void *hip_stream, size_t bytes, double *gbs);
 
 #ifdef __cplusplus

@@ -24,7 +24,7 @@ STATUS_NAMES = ["AG_OK", "AG_EINVAL", "AG_EUNSUPPORTED", "AG_ECAPACITY", "AG_EWO
 
 EXPORTS = ["ag_create", "ag_destroy", "ag_last_error", "ag_workspace_bytes", "ag_poll_error",
            "ag_timing_kernels", "ag_timing_kernel_name", "ag_timing_enable", "ag_timing_read",
-           "ag_probe_mfma", "ag_probe_mfma_data", "ag_probe_copy", "ag_gate", "ag_rmsnorm_gate", "ag_compact_kv", "ag_pack_row_off", "ag_prefill_attn", "ag_prefill_attn_recent",
+           "ag_probe_mfma", "ag_probe_mfma_data", "ag_probe_mfma_duty", "ag_probe_copy", "ag_gate", "ag_rmsnorm_gate", "ag_compact_kv", "ag_pack_row_off", "ag_prefill_attn", "ag_prefill_attn_recent",
            "ag_compact_prefill_attn", "ag_project_compact_kv", "ag_project_compact_workspace_bytes", "ag_decode_attn", "ag_decode_attn_static", "ag_decode_static_scratch_bytes", "ag_decode_scratch_bytes", "ag_recent_fill", "ag_decode_attn_recent", "ag_gate_mha", "ag_gate_mha_workspace_bytes"]
 
 
@@ -79,6 +79,8 @@ def load() -> C.CDLL:
     lib.ag_probe_mfma.argtypes = [vp, vp, i32, C.POINTER(C.c_double)]
     lib.ag_probe_mfma_data.restype = C.c_int
     lib.ag_probe_mfma_data.argtypes = [vp, vp, i32, C.POINTER(C.c_double)]
+    lib.ag_probe_mfma_duty.restype = C.c_int
+    lib.ag_probe_mfma_duty.argtypes = [vp, vp, i32, i32, C.POINTER(C.c_double)]
     lib.ag_probe_copy.restype = C.c_int
     lib.ag_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_double)]
     lib.ag_gate.restype = C.c_int
@@ -206,6 +208,12 @@ class Context:
         """The same loop on operands that change per MFMA and look like data (the ceiling under the power cap)."""
         out = C.c_double()
         self._check(self._lib.ag_probe_mfma_data(self._h, _stream_ptr(stream), iters, C.byref(out)))
+        return out.value
+
+    def probe_mfma_duty(self, idle: int, iters: int = 20000, stream=None) -> float:
+        """The data-operand MFMA loop at one wave per SIMD, sleeping idle x 64 cycles after every 8 MFMAs; TFLOP/s."""
+        out = C.c_double(0.0)
+        self._check(self._lib.ag_probe_mfma_duty(self._h, _stream_ptr(stream), iters, idle, C.byref(out)))
         return out.value
 
     def probe_copy(self, nbytes: int, stream=None) -> float:

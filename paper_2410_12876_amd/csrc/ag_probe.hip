@@ -35,8 +35,11 @@ __global__ __launch_bounds__(256) void ag_probe_mfma_kernel(int iters, float *si
 // The same loop on operands that change from one MFMA to the next and look like data: eight A and eight B fragments
 // per lane with pseudo-random signs, mantissas and exponents (values of magnitude 1/4 .. 4), cycled so that
 // consecutive MFMAs of the matrix pipe never see the same inputs.  The power an MFMA draws depends on how many
-// bits toggle, so this is the ceiling that applies to a kernel working on real activations.
-__global__ __launch_bounds__(256) void ag_probe_mfma_data_kernel(int iters, float *sink) {
+// bits toggle, so this is the ceiling that applies to a kernel working on real activations.  idle > 0: after every
+// 8 MFMAs the wave sleeps idle x 64 cycles, which sets the matrix pipe's duty cycle when one wave runs per SIMD
+// (256 busy cycles per group): the chip then clocks higher, and the pair (duty, rate) shows how the power budget
+// trades clock against activity.
+__global__ __launch_bounds__(256) void ag_probe_mfma_data_kernel(int iters, float *sink, int idle) {
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -60,6 +63,7 @@ __global__ __launch_bounds__(256) void ag_probe_mfma_data_kernel(int iters, floa
     for (int j = 0; j < 8; ++j)
       acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[j]),
                                                            __builtin_bit_cast(bf16x8, b[(j * 3 + 1) & 7]), acc[j & 3], 0, 0, 0);
+    for (int p = 0; p < idle; ++p) __builtin_amdgcn_s_sleep(1);
   }
   float s = 0.f;
 #pragma unroll
@@ -79,17 +83,23 @@ __global__ __launch_bounds__(256) void ag_probe_copy_kernel(const uint4 *__restr
 
 extern "C" {
 
-static ag_status probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, bool data, double *tflops);
+static ag_status probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, bool data, int idle, double *tflops);
 
 ag_status ag_probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, double *tflops) {
-  return probe_mfma(ctx, hip_stream, iters, false, tflops);
+  return probe_mfma(ctx, hip_stream, iters, false, -1, tflops);
 }
 
 ag_status ag_probe_mfma_data(ag_ctx *ctx, void *hip_stream, int iters, double *tflops) {
-  return probe_mfma(ctx, hip_stream, iters, true, tflops);
+  return probe_mfma(ctx, hip_stream, iters, true, -1, tflops);
 }
 
-static ag_status probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, bool data, double *tflops) {
+ag_status ag_probe_mfma_duty(ag_ctx *ctx, void *hip_stream, int iters, int idle, double *tflops) {
+  if (idle < 0 || idle > 64) return AG_EINVAL;
+  return probe_mfma(ctx, hip_stream, iters, true, idle, tflops);
+}
+
+// idle < 0: two workgroups per CU (2 waves per SIMD), no pauses; idle >= 0: one per CU with idle x 64-cycle pauses
+static ag_status probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, bool data, int idle, double *tflops) {
   if (!ctx || !tflops || iters <= 0) return AG_EINVAL;
   iters = (iters + 1) & ~1;
   if (ctx->device < 0) return ag_fail(ctx, AG_EHIP, "context has no device");
@@ -97,12 +107,16 @@ static ag_status probe_mfma(ag_ctx *ctx, void *hip_stream, int iters, bool data,
   hipEvent_t e0, e1;
   if (hipSetDevice(ctx->device) != hipSuccess || hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
     return ag_fail(ctx, AG_EHIP, "ag_probe_mfma: event creation failed");
-  const int blocks = ctx->num_cu * 2;  // 8 waves per CU, 2 per SIMD
+  const int blocks = ctx->num_cu * (idle < 0 ? 2 : 1);  // 8 waves per CU, 2 per SIMD; or 4, 1 per SIMD
   float *sink = reinterpret_cast<float *>(ctx->d_err) + 8;
-  auto kernel = data ? ag_probe_mfma_data_kernel : ag_probe_mfma_kernel;
-  hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, s, (iters / 8 + 2) & ~1, sink);  // warm-up
+  const int pauses = idle < 0 ? 0 : idle;
+  auto launch = [&](int n) {
+    if (data) hipLaunchKernelGGL(ag_probe_mfma_data_kernel, dim3(blocks), dim3(256), 0, s, n, sink, pauses);
+    else hipLaunchKernelGGL(ag_probe_mfma_kernel, dim3(blocks), dim3(256), 0, s, n, sink);
+  };
+  launch((iters / 8 + 2) & ~1);  // warm-up
   (void)hipEventRecord(e0, s);
-  hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
+  launch(iters);
   (void)hipEventRecord(e1, s);
   float ms = 0.f;
   hipError_t e = hipEventSynchronize(e1);
