@@ -11,7 +11,7 @@ import oracle
 import paper_2410_12876_amd as ag
 import workloads as W
 from gpu_util import (DEV, attn_error, attn_rms_error, attn_tolerance, cache_from_host, dev, ensure_built, host_bits,
-                      host_f32, make_ctx, new_cache)
+                      host_f32, make_ctx, new_cache, torch_dtype)
 
 pytestmark = pytest.mark.gpu
 
@@ -950,6 +950,115 @@ def test_config2_full_size_step_as_the_benchmark_runs_it():
     decode_and_check(ctx, wl, cache, ref, ro, 1, 78, None)
     print("cfg2 step: %d of %d logits within 1e-3 of the threshold, %d flags differ there" %
           (int(near.sum()), near.size, int((got_flags != ref_flags).sum())))
+    ctx.close()
+
+
+# ----------------------------------------------------------------- the whole path on drawn shapes, packed caches
+def _pipeline_cases(n, seed):
+    g = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        dtype = "f32" if i % 4 == 3 else "bf16"
+        D = int(g.choice([64, 128]))
+        Hkv = int(g.choice([1, 2, 4]))
+        G = int(g.choice([1, 2, 4]))
+        cases.append(dict(dtype=dtype, D=D, B=int(g.integers(1, 4)), Hkv=Hkv, Hq=Hkv * G, L=int(g.integers(20, 420)),
+                          d_in=64 * int(g.integers(1, 9)), n_recent=int(g.choice([1, 3, 17, 64])), tau=float(g.choice([0.3, 0.5, 0.7])),
+                          n_sink=int(g.choice([0, 1])), steps=int(g.integers(3, 9)), seed=int(g.integers(1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _pipeline_cases(24, 900), ids=lambda c: "%s-D%d-B%d-Hq%d-Hkv%d-L%d-d%d-w%d" % (
+    c["dtype"], c["D"], c["B"], c["Hq"], c["Hkv"], c["L"], c["d_in"], c["n_recent"]))
+def test_whole_path_on_drawn_shapes_with_packed_caches_and_recent_window(case):
+    """Gate -> packed cache layout -> compaction -> windowed prefill over the cache -> decode steps with the ring of
+    recent tokens, every stage against the oracle, on drawn shapes (both dtypes and head dimensions, grouped heads,
+    window widths 1 .. 64, ragged lengths).  The later stages run on the flags the HIP gate produced; the units'
+    capacities are their kept rows + `steps`, so the decode fills the packed cache exactly when every token is kept."""
+    c = case
+    dtype, D, B, Hq, Hkv, L, d_in, n_recent, steps = c["dtype"], c["D"], c["B"], c["Hq"], c["Hkv"], c["L"], c["d_in"], c["n_recent"], c["steps"]
+    g = np.random.default_rng(c["seed"])
+    tdt = torch_dtype(dtype)
+    code = ag.AG_BF16 if dtype == "bf16" else ag.AG_F32
+    T = L + steps
+    x = W.store((0.5 * g.standard_normal((B, L, d_in))).astype(np.float32), dtype)
+    wg = W.store((g.standard_normal((d_in, Hkv)) / math.sqrt(d_in)).astype(np.float32), dtype)
+    bias = (0.3 * g.standard_normal(Hkv)).astype(np.float32)
+    q_all, k_all, v_all = (W.store(g.standard_normal((B, h, T, D)).astype(np.float32), dtype) for h in (Hq, Hkv, Hkv))
+    f_new = (g.random((B, Hkv, steps)) < 0.6).astype(np.uint8)
+    scale = 1.0 / math.sqrt(D)
+    U = B * Hkv
+    # gate
+    ctx = make_ctx(B, L, Hq, Hkv, D, code, d_in=d_in, cache_rows=U * T)
+    flags = torch.empty(B, Hkv, L, dtype=torch.uint8, device=DEV)
+    logits = torch.empty(B, L, Hkv, dtype=torch.float32, device=DEV)
+    ag.ag_gate(ctx, dev(x), dev(wg), torch.from_numpy(bias).to(DEV), c["tau"], c["n_sink"], logits, flags)
+    torch.cuda.synchronize()
+    ref_logits, ref_flags = oracle.gate(x.f32, wg.f32, bias, c["tau"], c["n_sink"])
+    assert np.abs(logits.cpu().numpy() - ref_logits).max() <= 2e-4
+    near = (np.abs(ref_logits - oracle.logit_threshold(c["tau"])) < 1e-3).transpose(0, 2, 1)
+    fl = flags.cpu().numpy()
+    if c["n_sink"]:
+        near[:, :, :c["n_sink"]] = False
+    assert np.array_equal(fl[~near], ref_flags[~near])
+    f_all = np.concatenate([fl, f_new], axis=2)
+    # packed layout
+    want_ro, need = oracle.packed_row_off(fl, steps, 10 ** 9)
+    total = int(need)
+    row_off = torch.zeros(U + 1, dtype=torch.int64, device=DEV)
+    ag.ag_pack_row_off(ctx, flags, steps, total, row_off)
+    torch.cuda.synchronize()
+    assert np.array_equal(row_off.cpu().numpy(), want_ro)
+    cache = ag.KVCache(torch.full((max(total, 1), D), float("nan"), dtype=tdt, device=DEV),
+                       torch.full((max(total, 1), D), float("nan"), dtype=tdt, device=DEV),
+                       torch.full((max(total, 1),), -1, dtype=torch.int32, device=DEV), row_off,
+                       torch.zeros(U, dtype=torch.int32, device=DEV), B, Hkv, D, total_rows=total)
+    dq, dk, dv = dev(q_all), dev(k_all), dev(v_all)
+    qp, kp, vp = dq[:, :, :L].contiguous(), dk[:, :, :L].contiguous(), dv[:, :, :L].contiguous()
+    ag.ag_compact_kv(ctx, kp, vp, flags, 0, cache)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    ref_cache, over = oracle.compact_kv(k_all.f32[:, :, :L], v_all.f32[:, :, :L], fl, want_ro)
+    assert over == 0 and np.array_equal(cache.len.cpu().numpy(), ref_cache.len)
+    gk, gi = host_f32(cache.k), cache.idx.cpu().numpy()
+    for u in range(U):
+        a, n = int(want_ro[u]), int(ref_cache.len[u])
+        assert np.array_equal(gk[a:a + n], ref_cache.k[a:a + n]) and np.array_equal(gi[a:a + n], ref_cache.idx[a:a + n])
+    # windowed prefill over the packed cache
+    out = torch.empty_like(qp)
+    ag.ag_prefill_attn_recent(ctx, qp, kp, vp, flags, scale, cache, n_recent, out)
+    torch.cuda.synchronize()
+    ctx.poll_error()
+    want = oracle.prefill_attn(q_all.f32[:, :, :L], k_all.f32[:, :, :L], v_all.f32[:, :, :L], fl, scale, n_recent=n_recent)
+    got = host_f32(out)
+    assert np.isfinite(got).all() and attn_error(dtype, got, want) <= attn_tolerance(dtype, want)
+    # decode with the ring
+    ring = None            # a window of one token is the plain decode: the ring holds the tokens BEFORE the current one
+    if n_recent > 1:
+        ring = ag.RecentRing(torch.zeros(U, n_recent, D, dtype=tdt, device=DEV), torch.zeros(U, n_recent, D, dtype=tdt, device=DEV),
+                             torch.zeros(U, n_recent, dtype=torch.uint8, device=DEV),
+                             torch.zeros(U, n_recent, dtype=torch.int32, device=DEV), n_recent)
+        ag.ag_recent_fill(ctx, kp, vp, flags, 0, ring)
+    o1 = torch.empty(B, Hq, D, dtype=tdt, device=DEV)
+    dfn = dev(f_new)
+    for s_ in range(steps):
+        p = L + s_
+        args = (dq[:, :, p].contiguous(), dk[:, :, p].contiguous(), dv[:, :, p].contiguous(), dfn[:, :, s_].contiguous(), p, scale, cache)
+        if ring is None:
+            ag.ag_decode_attn(ctx, *args, o1)
+        else:
+            ag.ag_decode_attn_recent(ctx, *args, ring, o1)
+        want1 = oracle.prefill_rows(q_all.f32[:, :, :p + 1], k_all.f32[:, :, :p + 1], v_all.f32[:, :, :p + 1],
+                                    f_all[:, :, :p + 1], scale, np.array([p]), n_recent=n_recent)[:, :, 0]
+        got1 = host_f32(o1)
+        assert np.isfinite(got1).all() and attn_error(dtype, got1, want1) <= attn_tolerance(dtype, want1), "step %d" % s_
+        _, dropped = oracle.decode_step(q_all.f32[:, :, p], k_all.f32[:, :, p], v_all.f32[:, :, p], f_new[:, :, s_], p, ref_cache, scale)
+        assert dropped == 0 and np.array_equal(cache.len.cpu().numpy(), ref_cache.len)
+    ctx.poll_error()
+    gk, gi = host_f32(cache.k), cache.idx.cpu().numpy()
+    for u in range(U):
+        a, n = int(want_ro[u]), int(ref_cache.len[u])
+        assert np.array_equal(gk[a:a + n], ref_cache.k[a:a + n]) and np.array_equal(gi[a:a + n], ref_cache.idx[a:a + n])
     ctx.close()
 
 
